@@ -1,0 +1,229 @@
+"""Seeded synthetic inputs for the ASL token-importance pass.
+
+This module only *draws inputs*: it holds none of the method's arithmetic (no
+softmax, pooling, ranking, selection).  Both the CPU oracle's tests and the HIP
+path's tests/bench feed on it, so the two sides read exactly the same bits.
+
+The workloads stand in for the paper's long-context evaluation (Sec. 5.1 and
+App. C: context 4k-256k, observation window 32, pooling kernel 7, KV budget
+2048, Llama-3.1-8B head geometry from App. B.3): only the *shapes* are taken,
+all values are random.
+
+Every generator uses numpy ``Generator(PCG64(seed))``; values are drawn in
+fp32 and, for the bf16 workloads, rounded to bf16 (round-to-nearest-even) once
+so that the float arrays returned here are exactly representable in bf16.
+"""
+from __future__ import annotations
+
+import math
+from dataclasses import dataclass, field
+
+import numpy as np
+
+BASE_SEED = 20260100
+
+
+# --------------------------------------------------------------------------- bf16 helpers
+def bf16_bits(x: np.ndarray) -> np.ndarray:
+    """fp32 array -> uint16 bf16 bit patterns, round-to-nearest-even (finite inputs)."""
+    u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32)
+    r = (u + np.uint32(0x7FFF) + ((u >> np.uint32(16)) & np.uint32(1))) >> np.uint32(16)
+    return r.astype(np.uint16)
+
+
+def bf16_to_f32(bits: np.ndarray) -> np.ndarray:
+    """uint16 bf16 bit patterns -> fp32 array (exact)."""
+    return (bits.astype(np.uint32) << np.uint32(16)).view(np.float32)
+
+
+def round_bf16(x: np.ndarray) -> np.ndarray:
+    """fp32 array -> fp32 array whose values are exactly bf16-representable."""
+    return bf16_to_f32(bf16_bits(x))
+
+
+# --------------------------------------------------------------------------- containers
+@dataclass
+class Shape:
+    """Problem statement of Alg. 1 / Alg. 2 (names follow the paper's notation)."""
+    Hq: int            # query heads
+    Hk: int            # KV heads
+    d: int             # head dim
+    N: int             # sequence length N_q
+    W: int             # observation window
+    S: int             # pooling kernel
+    budget: int        # KV budget
+    dtype: str = "bf16"          # "bf16" or "f32": storage type of Q/K/V
+    L_min: int = 10
+    L_obs: int = 8
+    tau: float = 0.3
+    n_layers: int = 1
+
+    @property
+    def G(self) -> int:
+        return self.Hq // self.Hk
+
+    @property
+    def T(self) -> int:
+        return self.N - self.W
+
+    @property
+    def k(self) -> int:
+        return min(self.budget, self.N) - self.W
+
+    @property
+    def scale(self) -> float:
+        return 1.0 / math.sqrt(self.d)
+
+
+@dataclass
+class Layer:
+    """One layer's inputs.  q_obs [Hq,W,d], k/v [Hk,N,d]; fp32 arrays whose values are
+    exactly representable in ``shape.dtype``."""
+    shape: Shape
+    q_obs: np.ndarray
+    k: np.ndarray
+    v: np.ndarray
+    needles: np.ndarray = field(default_factory=lambda: np.zeros(0, dtype=np.int64))
+    name: str = ""
+
+
+def _finish(shape: Shape, x: np.ndarray) -> np.ndarray:
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    return round_bf16(x) if shape.dtype == "bf16" else x
+
+
+def _normal(rng: np.random.Generator, *dims: int) -> np.ndarray:
+    return rng.standard_normal(dims, dtype=np.float32)
+
+
+def _plant_needles(rng, shape: Shape, q_obs: np.ndarray, k: np.ndarray, n_needles: int,
+                   gain: float, sigma: float = 0.1, sep: int = 4) -> np.ndarray:
+    """Pick ``n_needles`` distinct past positions, at least ``sep`` apart and ``sep`` from
+    both ends, and overwrite K there with gain * (mean observation query of the group) +
+    N(0, sigma^2).  Returns the sorted positions."""
+    T = shape.T
+    assert n_needles * sep * 2 < T
+    # Draw on a coarse grid of spacing `sep` so the separation holds by construction.
+    cells = rng.choice((T - 2 * sep) // sep, size=n_needles, replace=False)
+    pos = np.sort(sep + cells.astype(np.int64) * sep)
+    G, W, d = shape.G, shape.W, shape.d
+    for g in range(shape.Hk):
+        m_g = q_obs[g * G:(g + 1) * G].reshape(G * W, d).mean(axis=0, dtype=np.float64)
+        noise = sigma * _normal(rng, n_needles, d)
+        k[g, pos, :] = (gain * m_g).astype(np.float32)[None, :] + noise
+    return pos
+
+
+# --------------------------------------------------------------------------- the five configs
+def shape_of(config: int) -> Shape:
+    if config == 1:
+        return Shape(Hq=4, Hk=2, d=64, N=512, W=16, S=7, budget=128, dtype="f32",
+                     L_min=2, L_obs=3)
+    if config == 2:
+        return Shape(Hq=32, Hk=8, d=128, N=32768, W=32, S=7, budget=2048)
+    if config == 3:
+        return Shape(Hq=32, Hk=8, d=128, N=131072, W=32, S=7, budget=2048)
+    if config == 4:
+        return Shape(Hq=32, Hk=8, d=128, N=32768, W=32, S=7, budget=1024, n_layers=32)
+    if config == 5:
+        return Shape(Hq=32, Hk=8, d=128, N=262144, W=64, S=7, budget=4096)
+    raise ValueError(f"unknown config {config}")
+
+
+def iid_layer(shape: Shape, seed: int, name: str = "") -> Layer:
+    """Q_obs, K, V i.i.d. N(0,1)."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    q = _finish(shape, _normal(rng, shape.Hq, shape.W, shape.d))
+    k = _finish(shape, _normal(rng, shape.Hk, shape.N, shape.d))
+    v = _finish(shape, _normal(rng, shape.Hk, shape.N, shape.d))
+    return Layer(shape, q, k, v, name=name)
+
+
+def needle_layer(shape: Shape, seed: int, n_needles: int, gain: float,
+                 heavy_tail: bool = False, name: str = "") -> Layer:
+    """i.i.d. N(0,1) layer, optionally with a per-token lognormal(0,1) key scale shared by
+    all KV heads, then ``n_needles`` planted keys (planted after the scaling)."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    q = _finish(shape, _normal(rng, shape.Hq, shape.W, shape.d))
+    k = _normal(rng, shape.Hk, shape.N, shape.d)
+    v = _finish(shape, _normal(rng, shape.Hk, shape.N, shape.d))
+    if heavy_tail:
+        tok_scale = np.exp(_normal(rng, shape.N)).astype(np.float32)
+        k *= tok_scale[None, :, None]
+    pos = _plant_needles(rng, shape, q, k, n_needles, gain)
+    return Layer(shape, q, _finish(shape, k), v, needles=pos, name=name)
+
+
+# Gain 4 is the recipe as literally stated for the workloads; at that gain a needle's
+# expected logit is *below* an average key's, so it is not recoverable by any correct
+# implementation.  The strong gain 4*sqrt(d) makes the exact-index check meaningful.
+NEEDLE_GAIN_LITERAL = 4.0
+
+
+def needle_gain_strong(shape: Shape) -> float:
+    return 4.0 * math.sqrt(shape.d)
+
+
+def config_layer(config: int, strong_needles: bool = True) -> Layer:
+    """Single-layer configs 1, 2, 3, 5."""
+    shape = shape_of(config)
+    seed = BASE_SEED + config
+    if config == 1:
+        return iid_layer(shape, seed, name="C1-tiny")
+    if config == 2:
+        return iid_layer(shape, seed, name="C2-8B-32K")
+    if config in (3, 5):
+        gain = needle_gain_strong(shape) if strong_needles else NEEDLE_GAIN_LITERAL
+        n_needles = 64 if config == 3 else 256
+        tag = "strong" if strong_needles else "literal"
+        nm = ("C3-8B-128K-needles-" if config == 3 else "C5-8B-256K-heavytail-needles-") + tag
+        return needle_layer(shape, seed, n_needles, gain, heavy_tail=(config == 5), name=nm)
+    raise ValueError("config 4 is a multi-layer sweep: use sweep_latents / sweep_layer")
+
+
+# --------------------------------------------------------------------------- config 4: layer sweep
+def sweep_rho(layer: int, n_layers: int = 32) -> float:
+    """Linear correlation schedule 0.2 -> 0.95 over the layers."""
+    return 0.2 + 0.75 * layer / (n_layers - 1)
+
+
+def sweep_latents(T: int, n_layers: int = 32, seed: int = BASE_SEED + 4) -> np.ndarray:
+    """AR(1) latent importance z_l in R^T per layer: z_l = rho_l z_{l-1} + sqrt(1-rho_l^2) eps_l,
+    z_{-1} a shared seeded N(0,1) vector.  Returns [n_layers, T] float64."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    z = rng.standard_normal(T)
+    out = np.empty((n_layers, T), dtype=np.float64)
+    for l in range(n_layers):
+        rho = sweep_rho(l, n_layers)
+        z = rho * z + math.sqrt(1.0 - rho * rho) * rng.standard_normal(T)
+        out[l] = z
+    return out
+
+
+def sweep_layer(shape: Shape, z_l: np.ndarray, layer: int, seed: int = BASE_SEED + 4) -> Layer:
+    """Q_obs / K of one sweep layer whose window logits follow the latent z_l:
+    Q_obs[h,i] = c u_g + 0.5 N(0,I), K[g,j] = a z_l[j] u_g + 0.5 N(0,I), a c / sqrt(d) = 1,
+    u_g a random unit vector per KV head.  Window keys (j >= T) get latent 0."""
+    rng = np.random.Generator(np.random.PCG64(seed * 1000 + layer + 1))
+    Hq, Hk, G, d, N, W, T = shape.Hq, shape.Hk, shape.G, shape.d, shape.N, shape.W, shape.T
+    a = c = d ** 0.25
+    u = rng.standard_normal((Hk, d))
+    u /= np.linalg.norm(u, axis=1, keepdims=True)
+    u = u.astype(np.float32)
+    zfull = np.zeros(N, dtype=np.float32)
+    zfull[:T] = z_l.astype(np.float32)
+    q = 0.5 * _normal(rng, Hq, W, d)
+    for h in range(Hq):
+        q[h] += c * u[h // G][None, :]
+    k = 0.5 * _normal(rng, Hk, N, d)
+    for g in range(Hk):
+        k[g] += (a * zfull)[:, None] * u[g][None, :]
+    v = _normal(rng, Hk, N, d)
+    return Layer(shape, _finish(shape, q), _finish(shape, k), _finish(shape, v),
+                 name=f"C4-sweep-L{layer}")
+
+
+def sweep_scores(z_l: np.ndarray) -> np.ndarray:
+    """Score-level variant of the sweep: a positive score vector with the order of z_l
+    (fp32, fed directly to the rank / statistic stage)."""
+    return np.exp(z_l).astype(np.float32)
