@@ -1,0 +1,160 @@
+/*
+ * libasl -- the per-layer token-importance pass of Adaptive Selection Layer (ASL) token pruning
+ * (arXiv 2601.07667), as hand-written HIP kernels for gfx950 (MI355X) behind a C ABI.
+ *
+ * The calls follow the problem statement of the paper's Alg. 1 (GetRanks: Q, K, V, layer_idx,
+ * window W, pooling kernel S, KV budget, rank cache) and Alg. 2 (SelectTokens: layer_idx,
+ * KV budget, W, L_min, L_obs, tau, rank cache, init_var).
+ *
+ * Conventions for every entry point
+ *  - Pointers named q_obs, k, v, lse, u, p_head, s_all, scores, rank*, idx*, state, out are
+ *    DEVICE pointers owned by the caller.  `params` and `ctx` are HOST pointers.  The library
+ *    owns only the workspace inside asl_ctx (allocated by asl_create; no allocation afterwards).
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls enqueue work
+ *    and return; they never synchronise.  One asl_ctx must be used by one stream at a time
+ *    (calls sharing a ctx share its workspace and race if they overlap).
+ *  - Return value: ASL_OK or a negative asl_status.  Arguments are validated on the host before
+ *    any launch; asl_last_error() gives a message for the last failure on that ctx.
+ *  - Notation: Hq query heads, Hk KV heads, G = Hq/Hk, d head dim, N sequence length,
+ *    W window, T = N - W past tokens, S pooling kernel, k = min(budget, N) - W.
+ *  - Tie rule everywhere: among equal scores the lower token index ranks first / is kept.
+ *    NaN scores give an unspecified (but memory-safe) order.
+ */
+#ifndef ASL_H_
+#define ASL_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct asl_ctx asl_ctx;
+
+typedef enum {
+  ASL_OK = 0,
+  ASL_EINVAL = -1,        /* bad argument (null pointer, shape, budget <= W, even S, ...) */
+  ASL_ENOMEM = -2,        /* workspace allocation failed / problem larger than the ctx was made for */
+  ASL_EHIP = -3,          /* a HIP runtime call failed */
+  ASL_EUNSUPPORTED = -4   /* valid but not implemented (dtype, misaligned strides, sizes past limits) */
+} asl_status;
+
+typedef enum { ASL_BF16 = 0, ASL_F32 = 1 } asl_dtype;
+
+/* Problem statement (Alg. 1 inputs; Alg. 2 shares budget and window). */
+typedef struct {
+  int32_t n_q_heads;      /* Hq                                            */
+  int32_t n_kv_heads;     /* Hk, Hq % Hk == 0                              */
+  int32_t head_dim;       /* d                                             */
+  int32_t seq_len;        /* N = N_q (keys == queries during prefill)      */
+  int32_t window;         /* W, 1 <= W < N                                 */
+  int32_t pool_kernel;    /* S, odd, >= 1                                  */
+  int32_t budget;         /* KV budget, > W;  k = min(budget, N) - W       */
+  int32_t dtype;          /* asl_dtype of q_obs, k, v                      */
+  int64_t k_stride_head;  /* element strides of K [Hk, N, d]; d contiguous */
+  int64_t k_stride_tok;
+  int64_t v_stride_head;  /* same for V                                    */
+  int64_t v_stride_tok;
+  float scale;            /* logit scale; <= 0 means 1/sqrt(d)             */
+  int32_t flags;          /* ASL_FLAG_* bits, normally 0                   */
+} asl_params;
+
+/* Score with the plain fp32-FMA kernels even where the MFMA kernels apply (an on-GPU cross-check). */
+#define ASL_FLAG_GENERIC_SCORE 1
+
+/* Cross-layer state of Alg. 2 (init_var and the fill level of the rank cache).  24-byte device
+ * struct owned by the caller; all-zero bytes = fresh sequence.  The library updates it. */
+typedef struct {
+  double init_var;        /* var_top at the first evaluated layer (Sec. 4.1, relative variance) */
+  int32_t init_set;       /* 0 until init_var has been set                                      */
+  int32_t n_valid_rows;   /* filled rows of the rank ring, <= L_obs                             */
+  int32_t last_layer;     /* layer index of the newest row (valid when n_valid_rows > 0)        */
+  int32_t reserved;
+} asl_state;
+
+/* Result of the statistic (Alg. 2 steps 4-10), written to device memory. */
+typedef struct {
+  double var_top;         /* mean over the union of the per-token rank variance               */
+  double rel_var;         /* var_top / init_var (IEEE: NaN or inf when init_var == 0)         */
+  uint64_t numerator;     /* sum over the union of  n * sum R^2 - (sum R)^2  (exact)          */
+  int32_t union_size;     /* |top(L)|                                                         */
+  int32_t n_rows;         /* rank rows used (n)                                               */
+  int32_t evaluated;      /* 0 when layer_idx < L_min or fewer than two rows were available   */
+  int32_t selected;       /* 1 iff evaluated and rel_var < tau                                */
+} asl_stat;
+
+/* Create a context on `device` with a workspace large enough for any call with
+ * seq_len <= max_seq_len, n_kv_heads <= max_kv_heads and Hq*W <= max_q_rows.
+ * Errors: ASL_EINVAL (null/negative), ASL_EHIP, ASL_ENOMEM. */
+asl_status asl_create(asl_ctx** out, int device, int32_t max_seq_len, int32_t max_kv_heads,
+                      int32_t max_q_rows);
+asl_status asl_destroy(asl_ctx* ctx);
+/* Message of the last failure on ctx (ctx-owned string, valid until the next call on ctx). */
+const char* asl_last_error(const asl_ctx* ctx);
+/* Bytes of device workspace asl_create would allocate for these limits. */
+size_t asl_workspace_bytes(int32_t max_seq_len, int32_t max_kv_heads, int32_t max_q_rows);
+
+/* Alg. 1 steps 5-8 and the Sec. 4.1 "scores" equation.
+ *   q_obs  [Hq, W, d] contiguous: the last W query rows of every head.
+ *   k      [Hk, N, d] with the strides in params (16-byte aligned rows).
+ *   lse    [Hq, W] f32 or NULL: natural-log-sum-exp of each window row's masked, scaled logits
+ *          (what the layer's attention kernel produces).  When given, K is streamed once;
+ *          when NULL the row normalisers are computed here with an extra pass over K.
+ *   p_head [Hk, T] f32 out: pooled, group-summed scores P.
+ *   s_all  [T]     f32 out: sum of P over the KV heads (the vector that is ranked).
+ * Logits are scaled q.k with the causal mask on the last W x W block; softmax over all N keys;
+ * column sums over the W rows and the G heads of a group, past columns only; AvgPool1D(S,
+ * stride 1, zero pad floor(S/2), divisor S).  bf16 inputs use bf16 MFMA with fp32 accumulation;
+ * softmax and sums are fp32 and deterministic (fixed reduction order, no float atomics). */
+asl_status asl_score_layer(asl_ctx* ctx, const asl_params* params, const void* q_obs,
+                           const void* k, const float* lse, float* p_head, float* s_all,
+                           void* stream);
+
+/* Alg. 1 step 7 on its own: zero-padded moving average, kernel S (odd), stride 1, along T.
+ *   u [rows, T] f32 in; p_out [rows, T] f32 out; s_out [T] f32 out or NULL (sum of the pooled rows). */
+asl_status asl_pool(asl_ctx* ctx, const float* u, int32_t rows, int32_t T, int32_t S,
+                    float* p_out, float* s_out, void* stream);
+
+/* Alg. 1 step 11, RankDesc: rank_out[t] = #{t': s[t'] > s[t]} + #{t' < t: s[t'] == s[t]}.
+ *   s [T] f32 in; rank_out [T] int32 out (a permutation of 0..T-1). */
+asl_status asl_rank(asl_ctx* ctx, const float* s, int32_t T, int32_t* rank_out, void* stream);
+
+/* Alg. 2 steps 4-10 on a rank ring that already holds this layer's row.
+ *   rank_ring [l_obs, T] int32; the rows in use are those of layers
+ *   layer_idx - state->n_valid_rows + 1 .. layer_idx, layer l living in row l % l_obs.
+ *   Union = tokens with rank < k in any used row; var_top = mean population variance of their
+ *   ranks; first evaluation sets state->init_var; selected = (var_top / init_var < tau).
+ *   With layer_idx < l_min or fewer than two rows: out->evaluated = 0 and nothing else changes.
+ *   On selection the ring is released (state->n_valid_rows = 0).
+ * Limits: n^2 * T^3 / 4 must fit in 64 bits (ASL_EUNSUPPORTED otherwise). */
+asl_status asl_rankvar(asl_ctx* ctx, const int32_t* rank_ring, int32_t l_obs, int32_t T,
+                       int32_t layer_idx, int32_t l_min, int32_t k, double tau,
+                       asl_state* state, asl_stat* out, void* stream);
+
+/* Alg. 1 step 11 + Alg. 2: rank s_all into ring row layer_idx % l_obs (a layer index that does
+ * not follow state->last_layer restarts the ring), then the statistic as asl_rankvar with
+ * k = min(budget - W, T).  The host reads *out after synchronising the stream. */
+asl_status asl_rank_stat(asl_ctx* ctx, const asl_params* params, const float* s_all,
+                         int32_t layer_idx, int32_t l_min, int32_t l_obs, double tau,
+                         int32_t* rank_ring, asl_state* state, asl_stat* out, void* stream);
+
+/* Alg. 1 steps 9-10 (rows = Hk on p_head) or Alg. 2 steps 11-12 (rows = 1 on s_all):
+ *   scores  [rows, T] f32 in.
+ *   idx_out [rows, k + W] int32 out: the k highest-scoring past tokens of each row in ascending
+ *   token order, followed by the window tokens T .. T+W-1. */
+asl_status asl_select_topk(asl_ctx* ctx, const asl_params* params, const float* scores,
+                           int32_t rows, int32_t* idx_out, void* stream);
+
+/* Alg. 1 step 12: K[I], V[I].
+ *   idx [idx_rows, n_idx] int32, idx_rows in {1, Hk} (one shared row or one per KV head),
+ *   every entry in [0, N) (caller's contract; asl_select_topk output satisfies it).
+ *   k_out, v_out [Hk, n_idx, d] dense, same dtype as k, v.  v / v_out may both be NULL. */
+asl_status asl_gather_kv(asl_ctx* ctx, const asl_params* params, const void* k, const void* v,
+                         const int32_t* idx, int32_t idx_rows, int32_t n_idx, void* k_out,
+                         void* v_out, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ASL_H_ */

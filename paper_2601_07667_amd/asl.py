@@ -1,0 +1,183 @@
+"""ctypes binding of libasl.so: argument marshalling only.
+
+Every function takes torch CUDA tensors (device memory) and forwards their pointers to the
+C ABI declared in include/asl.h; all computation happens in the HIP kernels.  There is no CPU
+fallback: if the shared library is missing or a call fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libasl.so")
+
+ASL_OK, ASL_EINVAL, ASL_ENOMEM, ASL_EHIP, ASL_EUNSUPPORTED = 0, -1, -2, -3, -4
+ASL_BF16, ASL_F32 = 0, 1
+ASL_FLAG_GENERIC_SCORE = 1
+_STATUS = {0: "ASL_OK", -1: "ASL_EINVAL", -2: "ASL_ENOMEM", -3: "ASL_EHIP", -4: "ASL_EUNSUPPORTED"}
+
+EXPORTS = ["asl_create", "asl_destroy", "asl_last_error", "asl_workspace_bytes", "asl_score_layer",
+           "asl_pool", "asl_rank", "asl_rankvar", "asl_rank_stat", "asl_select_topk", "asl_gather_kv"]
+
+
+class AslParams(C.Structure):
+    _fields_ = [("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32),
+                ("seq_len", C.c_int32), ("window", C.c_int32), ("pool_kernel", C.c_int32),
+                ("budget", C.c_int32), ("dtype", C.c_int32),
+                ("k_stride_head", C.c_int64), ("k_stride_tok", C.c_int64),
+                ("v_stride_head", C.c_int64), ("v_stride_tok", C.c_int64),
+                ("scale", C.c_float), ("flags", C.c_int32)]
+
+
+class AslState(C.Structure):
+    _fields_ = [("init_var", C.c_double), ("init_set", C.c_int32), ("n_valid_rows", C.c_int32),
+                ("last_layer", C.c_int32), ("reserved", C.c_int32)]
+
+
+class AslStat(C.Structure):
+    _fields_ = [("var_top", C.c_double), ("rel_var", C.c_double), ("numerator", C.c_uint64),
+                ("union_size", C.c_int32), ("n_rows", C.c_int32), ("evaluated", C.c_int32),
+                ("selected", C.c_int32)]
+
+
+class AslError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"{_STATUS.get(status, status)}: {message}")
+        self.status = status
+
+
+_lib = None
+
+
+def load() -> C.CDLL:
+    """Load libasl.so (built in-tree by paper_2601_07667_amd.build).  Fails loudly if absent."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} not found: build it with `python -m paper_2601_07667_amd.build`")
+    lib = C.CDLL(LIB_PATH)
+    vp, i32, i64 = C.c_void_p, C.c_int32, C.c_int64
+    lib.asl_create.argtypes = [C.POINTER(vp), C.c_int, i32, i32, i32]
+    lib.asl_create.restype = C.c_int
+    lib.asl_destroy.argtypes = [vp]
+    lib.asl_destroy.restype = C.c_int
+    lib.asl_last_error.argtypes = [vp]
+    lib.asl_last_error.restype = C.c_char_p
+    lib.asl_workspace_bytes.argtypes = [i32, i32, i32]
+    lib.asl_workspace_bytes.restype = C.c_size_t
+    lib.asl_score_layer.argtypes = [vp, C.POINTER(AslParams), vp, vp, vp, vp, vp, vp]
+    lib.asl_score_layer.restype = C.c_int
+    lib.asl_pool.argtypes = [vp, vp, i32, i32, i32, vp, vp, vp]
+    lib.asl_pool.restype = C.c_int
+    lib.asl_rank.argtypes = [vp, vp, i32, vp, vp]
+    lib.asl_rank.restype = C.c_int
+    lib.asl_rankvar.argtypes = [vp, vp, i32, i32, i32, i32, i32, C.c_double, vp, vp, vp]
+    lib.asl_rankvar.restype = C.c_int
+    lib.asl_rank_stat.argtypes = [vp, C.POINTER(AslParams), vp, i32, i32, i32, C.c_double, vp, vp, vp, vp]
+    lib.asl_rank_stat.restype = C.c_int
+    lib.asl_select_topk.argtypes = [vp, C.POINTER(AslParams), vp, i32, vp, vp]
+    lib.asl_select_topk.restype = C.c_int
+    lib.asl_gather_kv.argtypes = [vp, C.POINTER(AslParams), vp, vp, vp, i32, i32, vp, vp, vp]
+    lib.asl_gather_kv.restype = C.c_int
+    _lib = lib
+    return lib
+
+
+def _ptr(t) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+def _stream() -> int:
+    import torch
+    return torch.cuda.current_stream().cuda_stream
+
+
+def make_params(Hq: int, Hk: int, d: int, N: int, W: int, S: int, budget: int, dtype: int = ASL_BF16,
+                k_strides=None, v_strides=None, scale: float = 0.0, flags: int = 0) -> AslParams:
+    ks = k_strides or (N * d, d)
+    vs = v_strides or (N * d, d)
+    return AslParams(Hq, Hk, d, N, W, S, budget, dtype, ks[0], ks[1], vs[0], vs[1], scale, flags)
+
+
+class Asl:
+    """One libasl context (device workspace) and thin wrappers around its entry points."""
+
+    def __init__(self, max_seq_len: int, max_kv_heads: int, max_q_rows: int, device: int = 0):
+        self.lib = load()
+        h = C.c_void_p()
+        st = self.lib.asl_create(C.byref(h), device, max_seq_len, max_kv_heads, max_q_rows)
+        if st != ASL_OK:
+            raise AslError(st, "asl_create failed")
+        self.h = h
+        self.device = device
+
+    def close(self) -> None:
+        if getattr(self, "h", None):
+            self.lib.asl_destroy(self.h)
+            self.h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def _check(self, st: int) -> None:
+        if st != ASL_OK:
+            raise AslError(st, self.lib.asl_last_error(self.h).decode())
+
+    # -- entry points (same names as the C ABI) ------------------------------------------------
+    def asl_score_layer(self, params: AslParams, q_obs, k, p_head, s_all, lse=None) -> None:
+        self._check(self.lib.asl_score_layer(self.h, C.byref(params), _ptr(q_obs), _ptr(k), _ptr(lse),
+                                             _ptr(p_head), _ptr(s_all), _stream()))
+
+    def asl_pool(self, u, rows: int, T: int, S: int, p_out, s_out=None) -> None:
+        self._check(self.lib.asl_pool(self.h, _ptr(u), rows, T, S, _ptr(p_out), _ptr(s_out), _stream()))
+
+    def asl_rank(self, s, T: int, rank_out) -> None:
+        self._check(self.lib.asl_rank(self.h, _ptr(s), T, _ptr(rank_out), _stream()))
+
+    def asl_rankvar(self, rank_ring, l_obs: int, T: int, layer_idx: int, l_min: int, k: int, tau: float,
+                    state, out) -> None:
+        self._check(self.lib.asl_rankvar(self.h, _ptr(rank_ring), l_obs, T, layer_idx, l_min, k, tau,
+                                         _ptr(state), _ptr(out), _stream()))
+
+    def asl_rank_stat(self, params: AslParams, s_all, layer_idx: int, l_min: int, l_obs: int, tau: float,
+                      rank_ring, state, out) -> None:
+        self._check(self.lib.asl_rank_stat(self.h, C.byref(params), _ptr(s_all), layer_idx, l_min, l_obs,
+                                           tau, _ptr(rank_ring), _ptr(state), _ptr(out), _stream()))
+
+    def asl_select_topk(self, params: AslParams, scores, rows: int, idx_out) -> None:
+        self._check(self.lib.asl_select_topk(self.h, C.byref(params), _ptr(scores), rows, _ptr(idx_out),
+                                             _stream()))
+
+    def asl_gather_kv(self, params: AslParams, k, v, idx, idx_rows: int, n_idx: int, k_out, v_out) -> None:
+        self._check(self.lib.asl_gather_kv(self.h, C.byref(params), _ptr(k), _ptr(v), _ptr(idx), idx_rows,
+                                           n_idx, _ptr(k_out), _ptr(v_out), _stream()))
+
+
+# -- helpers for the device-resident structs (plumbing only) ---------------------------------------
+def new_state(device="cuda:0"):
+    """A zeroed asl_state in device memory (24 bytes)."""
+    import torch
+    return torch.zeros(C.sizeof(AslState), dtype=torch.uint8, device=device)
+
+
+def new_stat(device="cuda:0"):
+    import torch
+    return torch.zeros(C.sizeof(AslStat), dtype=torch.uint8, device=device)
+
+
+def read_struct(t, cls):
+    """Copy a device-resident struct to the host (synchronises)."""
+    return cls.from_buffer_copy(bytes(t.cpu().numpy().tobytes()))
+
+
+def write_state(t, init_var: float = 0.0, init_set: int = 0, n_valid_rows: int = 0, last_layer: int = 0):
+    import numpy as np
+    import torch
+    s = AslState(init_var, init_set, n_valid_rows, last_layer, 0)
+    t.copy_(torch.from_numpy(np.frombuffer(bytes(s), dtype=np.uint8).copy()))

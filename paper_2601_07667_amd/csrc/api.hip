@@ -1,0 +1,325 @@
+// The C ABI of libasl: context/workspace management, host-side argument validation, and the
+// launch sequences behind each entry point declared in include/asl.h.
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+
+#include "asl_internal.h"
+
+struct asl_ctx {
+  int device;
+  int32_t max_seq_len, max_kv_heads, max_q_rows;
+  void* base;
+  size_t bytes;
+  asl::Workspace ws;
+  char err[256];
+};
+
+namespace {
+
+constexpr int kMaxSelectRows = 48;
+constexpr int kMaxPoolKernel = 129;
+
+size_t align_up(size_t x) { return (x + 255) & ~size_t(255); }
+
+// Lay the workspace out from `base` (may be null to only measure).  Returns total bytes.
+size_t carve(char* base, int32_t max_seq_len, int32_t max_kv_heads, int32_t max_q_rows,
+             asl::Workspace* ws) {
+  size_t off = 0;
+  auto take = [&](size_t bytes) -> void* {
+    void* p = base ? base + off : nullptr;
+    off += align_up(bytes);
+    return p;
+  };
+  const size_t N = (size_t)max_seq_len;
+  const size_t rows = (size_t)(max_kv_heads > 1 ? max_kv_heads : 1);
+  const size_t sort_tiles = (N + asl::kSortTile - 1) / asl::kSortTile;
+  const size_t sel_tiles = (N + asl::kSelTile - 1) / asl::kSelTile;
+  asl::Workspace w;
+  w.row_part = (float*)take((size_t)asl::kMaxChunks * max_q_rows * 2 * sizeof(float));
+  w.row_const = (float*)take((size_t)max_q_rows * sizeof(float));
+  w.u_group = (float*)take(rows * N * sizeof(float));
+  for (int i = 0; i < 2; ++i) {
+    w.sort_key[i] = (uint32_t*)take(N * sizeof(uint32_t));
+    w.sort_idx[i] = (uint32_t*)take(N * sizeof(uint32_t));
+  }
+  w.tile_hist = (uint32_t*)take(256 * sort_tiles * sizeof(uint32_t));
+  w.counters = (uint32_t*)take(asl::kCounterWords * sizeof(uint32_t));
+  w.sel_hist = (uint32_t*)take(rows * 256 * sizeof(uint32_t));
+  w.sel_state = (uint32_t*)take(rows * 4 * sizeof(uint32_t));
+  w.sel_tile_cnt = (uint32_t*)take(rows * sel_tiles * 2 * sizeof(uint32_t));
+  if (ws) *ws = w;
+  return off;
+}
+
+asl_status fail(asl_ctx* ctx, asl_status st, const char* fmt, ...) {
+  if (ctx) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(ctx->err, sizeof(ctx->err), fmt, ap);
+    va_end(ap);
+  }
+  return st;
+}
+
+asl_status hip_fail(asl_ctx* ctx, hipError_t e, const char* what) {
+  return fail(ctx, ASL_EHIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+// Makes ctx->device current for the duration of a call and restores the caller's device.
+struct DeviceGuard {
+  int prev = -1;
+  bool switched = false;
+  hipError_t err = hipSuccess;
+  explicit DeviceGuard(int dev) {
+    err = hipGetDevice(&prev);
+    if (err == hipSuccess && prev != dev) {
+      err = hipSetDevice(dev);
+      switched = (err == hipSuccess);
+    }
+  }
+  ~DeviceGuard() {
+    if (switched) (void)hipSetDevice(prev);
+  }
+};
+
+int elem_bytes(int dtype) { return dtype == ASL_BF16 ? 2 : 4; }
+
+// Shape checks shared by the entry points that take asl_params.
+asl_status check_params(asl_ctx* ctx, const asl_params* p) {
+  if (!ctx) return ASL_EINVAL;
+  if (!p) return fail(ctx, ASL_EINVAL, "params is null");
+  if (p->n_q_heads < 1 || p->n_kv_heads < 1 || p->n_q_heads % p->n_kv_heads != 0)
+    return fail(ctx, ASL_EINVAL, "need Hq >= 1, Hk >= 1, Hq %% Hk == 0 (Hq=%d Hk=%d)", p->n_q_heads,
+                p->n_kv_heads);
+  if (p->head_dim < 1) return fail(ctx, ASL_EINVAL, "head_dim must be >= 1");
+  if (p->window < 1 || p->seq_len <= p->window)
+    return fail(ctx, ASL_EINVAL, "need 1 <= W < N (W=%d N=%d)", p->window, p->seq_len);
+  if (p->pool_kernel < 1 || p->pool_kernel % 2 == 0)
+    return fail(ctx, ASL_EINVAL, "pool kernel S must be odd and >= 1 (S=%d)", p->pool_kernel);
+  if (p->budget <= p->window)
+    return fail(ctx, ASL_EINVAL, "budget must exceed the window (budget=%d W=%d)", p->budget, p->window);
+  if (p->dtype != ASL_BF16 && p->dtype != ASL_F32)
+    return fail(ctx, ASL_EUNSUPPORTED, "dtype %d not supported", p->dtype);
+  if (p->pool_kernel > kMaxPoolKernel)
+    return fail(ctx, ASL_EUNSUPPORTED, "pool kernel S > %d not supported", kMaxPoolKernel);
+  if (p->seq_len > ctx->max_seq_len || p->n_kv_heads > ctx->max_kv_heads ||
+      (int64_t)p->n_q_heads * p->window > ctx->max_q_rows)
+    return fail(ctx, ASL_ENOMEM, "problem (N=%d Hk=%d Hq*W=%lld) exceeds the context limits (%d, %d, %d)",
+                p->seq_len, p->n_kv_heads, (long long)p->n_q_heads * p->window, ctx->max_seq_len,
+                ctx->max_kv_heads, ctx->max_q_rows);
+  return ASL_OK;
+}
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+}  // namespace
+
+extern "C" {
+#pragma GCC visibility push(default)
+
+size_t asl_workspace_bytes(int32_t max_seq_len, int32_t max_kv_heads, int32_t max_q_rows) {
+  if (max_seq_len < 2 || max_kv_heads < 1 || max_q_rows < 1) return 0;
+  return carve(nullptr, max_seq_len, max_kv_heads, max_q_rows, nullptr);
+}
+
+asl_status asl_create(asl_ctx** out, int device, int32_t max_seq_len, int32_t max_kv_heads,
+                      int32_t max_q_rows) {
+  if (!out) return ASL_EINVAL;
+  *out = nullptr;
+  if (device < 0 || max_seq_len < 2 || max_kv_heads < 1 || max_q_rows < 1) return ASL_EINVAL;
+  if (max_kv_heads > kMaxSelectRows) return ASL_EUNSUPPORTED;
+  int n_dev = 0;
+  if (hipGetDeviceCount(&n_dev) != hipSuccess || device >= n_dev) return ASL_EHIP;
+  asl_ctx* ctx = new (std::nothrow) asl_ctx();
+  if (!ctx) return ASL_ENOMEM;
+  ctx->device = device;
+  ctx->max_seq_len = max_seq_len;
+  ctx->max_kv_heads = max_kv_heads;
+  ctx->max_q_rows = max_q_rows;
+  ctx->err[0] = 0;
+  DeviceGuard guard(device);
+  if (guard.err != hipSuccess) {
+    delete ctx;
+    return ASL_EHIP;
+  }
+  ctx->bytes = carve(nullptr, max_seq_len, max_kv_heads, max_q_rows, nullptr);
+  hipError_t e = hipMalloc(&ctx->base, ctx->bytes);
+  if (e != hipSuccess) {
+    (void)hipGetLastError();
+    delete ctx;
+    return e == hipErrorOutOfMemory ? ASL_ENOMEM : ASL_EHIP;
+  }
+  carve(static_cast<char*>(ctx->base), max_seq_len, max_kv_heads, max_q_rows, &ctx->ws);
+  // tickets, accumulators and select histograms must start at zero; the kernels that use them
+  // leave them at zero again
+  e = hipMemset(ctx->base, 0, ctx->bytes);
+  if (e != hipSuccess) {
+    (void)hipFree(ctx->base);
+    delete ctx;
+    return ASL_EHIP;
+  }
+  *out = ctx;
+  return ASL_OK;
+}
+
+asl_status asl_destroy(asl_ctx* ctx) {
+  if (!ctx) return ASL_EINVAL;
+  DeviceGuard guard(ctx->device);
+  hipError_t e = hipFree(ctx->base);
+  delete ctx;
+  return e == hipSuccess ? ASL_OK : ASL_EHIP;
+}
+
+const char* asl_last_error(const asl_ctx* ctx) { return ctx ? ctx->err : "null context"; }
+
+asl_status asl_score_layer(asl_ctx* ctx, const asl_params* p, const void* q_obs, const void* k,
+                           const float* lse, float* p_head, float* s_all, void* stream) {
+  asl_status st = check_params(ctx, p);
+  if (st != ASL_OK) return st;
+  if (!q_obs || !k || !p_head || !s_all) return fail(ctx, ASL_EINVAL, "null tensor pointer");
+  if (p->k_stride_tok < p->head_dim || p->k_stride_head < 0)
+    return fail(ctx, ASL_EINVAL, "k strides must satisfy stride_tok >= d, stride_head >= 0");
+  const int eb = elem_bytes(p->dtype);
+  if (asl::score_mfma_supported(*p) &&
+      (!aligned16(q_obs) || !aligned16(k) || (p->k_stride_tok * eb) % 16 != 0 ||
+       (p->k_stride_head * eb) % 16 != 0))
+    return fail(ctx, ASL_EUNSUPPORTED, "q_obs/k must be 16-byte aligned with 16-byte-multiple strides");
+  DeviceGuard guard(ctx->device);
+  if (guard.err != hipSuccess) return hip_fail(ctx, guard.err, "set device");
+  hipStream_t hs = static_cast<hipStream_t>(stream);
+  hipError_t e = asl::launch_score(*p, ctx->ws, q_obs, k, lse, hs);
+  if (e != hipSuccess) return hip_fail(ctx, e, "score launch");
+  const int T = p->seq_len - p->window;
+  e = asl::launch_pool(ctx->ws.u_group, p->n_kv_heads, T, p->pool_kernel, p_head, s_all, hs);
+  if (e != hipSuccess) return hip_fail(ctx, e, "pool launch");
+  return ASL_OK;
+}
+
+asl_status asl_pool(asl_ctx* ctx, const float* u, int32_t rows, int32_t T, int32_t S, float* p_out,
+                    float* s_out, void* stream) {
+  if (!ctx) return ASL_EINVAL;
+  if (!u || !p_out) return fail(ctx, ASL_EINVAL, "null tensor pointer");
+  if (rows < 1 || T < 1) return fail(ctx, ASL_EINVAL, "need rows >= 1 and T >= 1");
+  if (S < 1 || S % 2 == 0) return fail(ctx, ASL_EINVAL, "pool kernel S must be odd and >= 1 (S=%d)", S);
+  if (S > kMaxPoolKernel) return fail(ctx, ASL_EUNSUPPORTED, "pool kernel S > %d not supported", kMaxPoolKernel);
+  DeviceGuard guard(ctx->device);
+  if (guard.err != hipSuccess) return hip_fail(ctx, guard.err, "set device");
+  hipError_t e = asl::launch_pool(u, rows, T, S, p_out, s_out, static_cast<hipStream_t>(stream));
+  if (e != hipSuccess) return hip_fail(ctx, e, "pool launch");
+  return ASL_OK;
+}
+
+asl_status asl_rank(asl_ctx* ctx, const float* s, int32_t T, int32_t* rank_out, void* stream) {
+  if (!ctx) return ASL_EINVAL;
+  if (!s || !rank_out) return fail(ctx, ASL_EINVAL, "null tensor pointer");
+  if (T < 1) return fail(ctx, ASL_EINVAL, "need T >= 1");
+  if (T > ctx->max_seq_len) return fail(ctx, ASL_ENOMEM, "T=%d exceeds the context limit %d", T, ctx->max_seq_len);
+  DeviceGuard guard(ctx->device);
+  if (guard.err != hipSuccess) return hip_fail(ctx, guard.err, "set device");
+  hipError_t e = asl::launch_rank(ctx->ws, s, T, rank_out, static_cast<hipStream_t>(stream));
+  if (e != hipSuccess) return hip_fail(ctx, e, "rank launch");
+  return ASL_OK;
+}
+
+static asl_status rankvar_checks(asl_ctx* ctx, int32_t l_obs, int32_t T, int32_t layer_idx, int32_t k) {
+  if (l_obs < 2 || l_obs > 64) return fail(ctx, ASL_EINVAL, "need 2 <= L_obs <= 64 (L_obs=%d)", l_obs);
+  if (T < 1 || layer_idx < 0 || k < 1) return fail(ctx, ASL_EINVAL, "need T >= 1, layer_idx >= 0, k >= 1");
+  // sum over <= T tokens of n^2 * variance <= n^2 * T^2 / 4 each must fit in 64 bits
+  const long double bound = (long double)l_obs * l_obs * (long double)T * T * T / 4.0L;
+  if (bound >= 18446744073709551615.0L)
+    return fail(ctx, ASL_EUNSUPPORTED, "L_obs^2 * T^3 / 4 does not fit in 64 bits (L_obs=%d T=%d)", l_obs, T);
+  return ASL_OK;
+}
+
+asl_status asl_rankvar(asl_ctx* ctx, const int32_t* rank_ring, int32_t l_obs, int32_t T,
+                       int32_t layer_idx, int32_t l_min, int32_t k, double tau, asl_state* state,
+                       asl_stat* out, void* stream) {
+  if (!ctx) return ASL_EINVAL;
+  if (!rank_ring || !state || !out) return fail(ctx, ASL_EINVAL, "null pointer");
+  asl_status st = rankvar_checks(ctx, l_obs, T, layer_idx, k);
+  if (st != ASL_OK) return st;
+  DeviceGuard guard(ctx->device);
+  if (guard.err != hipSuccess) return hip_fail(ctx, guard.err, "set device");
+  hipStream_t hs = static_cast<hipStream_t>(stream);
+  hipError_t e = (layer_idx < l_min)
+                     ? asl::launch_stat_skip(out, hs)
+                     : asl::launch_rankvar(ctx->ws, rank_ring, l_obs, T, layer_idx, k, tau, state, out, hs);
+  if (e != hipSuccess) return hip_fail(ctx, e, "rankvar launch");
+  return ASL_OK;
+}
+
+asl_status asl_rank_stat(asl_ctx* ctx, const asl_params* p, const float* s_all, int32_t layer_idx,
+                         int32_t l_min, int32_t l_obs, double tau, int32_t* rank_ring,
+                         asl_state* state, asl_stat* out, void* stream) {
+  asl_status st = check_params(ctx, p);
+  if (st != ASL_OK) return st;
+  if (!s_all || !rank_ring || !state || !out) return fail(ctx, ASL_EINVAL, "null pointer");
+  const int T = p->seq_len - p->window;
+  const int k = (p->budget < p->seq_len ? p->budget : p->seq_len) - p->window;
+  st = rankvar_checks(ctx, l_obs, T, layer_idx, k);
+  if (st != ASL_OK) return st;
+  DeviceGuard guard(ctx->device);
+  if (guard.err != hipSuccess) return hip_fail(ctx, guard.err, "set device");
+  hipStream_t hs = static_cast<hipStream_t>(stream);
+  int32_t* row = rank_ring + (int64_t)(layer_idx % l_obs) * T;
+  hipError_t e = asl::launch_rank(ctx->ws, s_all, T, row, hs);
+  if (e != hipSuccess) return hip_fail(ctx, e, "rank launch");
+  e = asl::launch_ring_push(state, layer_idx, l_obs, hs);
+  if (e != hipSuccess) return hip_fail(ctx, e, "ring push launch");
+  e = (layer_idx < l_min) ? asl::launch_stat_skip(out, hs)
+                          : asl::launch_rankvar(ctx->ws, rank_ring, l_obs, T, layer_idx, k, tau, state, out, hs);
+  if (e != hipSuccess) return hip_fail(ctx, e, "rankvar launch");
+  return ASL_OK;
+}
+
+asl_status asl_select_topk(asl_ctx* ctx, const asl_params* p, const float* scores, int32_t rows,
+                           int32_t* idx_out, void* stream) {
+  asl_status st = check_params(ctx, p);
+  if (st != ASL_OK) return st;
+  if (!scores || !idx_out) return fail(ctx, ASL_EINVAL, "null tensor pointer");
+  if (rows < 1) return fail(ctx, ASL_EINVAL, "need rows >= 1");
+  if (rows > ctx->max_kv_heads && rows > 1)
+    return fail(ctx, ASL_ENOMEM, "rows=%d exceeds the context limit %d", rows, ctx->max_kv_heads);
+  const int T = p->seq_len - p->window;
+  const int k = (p->budget < p->seq_len ? p->budget : p->seq_len) - p->window;
+  DeviceGuard guard(ctx->device);
+  if (guard.err != hipSuccess) return hip_fail(ctx, guard.err, "set device");
+  hipError_t e = asl::launch_select(ctx->ws, scores, rows, T, k, p->window, idx_out,
+                                    static_cast<hipStream_t>(stream));
+  if (e != hipSuccess) return hip_fail(ctx, e, "select launch");
+  return ASL_OK;
+}
+
+asl_status asl_gather_kv(asl_ctx* ctx, const asl_params* p, const void* k, const void* v,
+                         const int32_t* idx, int32_t idx_rows, int32_t n_idx, void* k_out,
+                         void* v_out, void* stream) {
+  asl_status st = check_params(ctx, p);
+  if (st != ASL_OK) return st;
+  if (!k || !idx || !k_out) return fail(ctx, ASL_EINVAL, "null tensor pointer");
+  if ((v == nullptr) != (v_out == nullptr)) return fail(ctx, ASL_EINVAL, "v and v_out must both be given or both be null");
+  if (idx_rows != 1 && idx_rows != p->n_kv_heads)
+    return fail(ctx, ASL_EINVAL, "idx_rows must be 1 or Hk (got %d)", idx_rows);
+  if (n_idx < 0) return fail(ctx, ASL_EINVAL, "n_idx must be >= 0");
+  const int eb = elem_bytes(p->dtype);
+  const int64_t row_bytes = (int64_t)p->head_dim * eb;
+  if (row_bytes % 16 != 0 || !aligned16(k) || !aligned16(k_out) || (p->k_stride_tok * eb) % 16 != 0 ||
+      (p->k_stride_head * eb) % 16 != 0 ||
+      (v && (!aligned16(v) || !aligned16(v_out) || (p->v_stride_tok * eb) % 16 != 0 ||
+             (p->v_stride_head * eb) % 16 != 0)))
+    return fail(ctx, ASL_EUNSUPPORTED, "gather needs 16-byte aligned rows, pointers and strides");
+  if (p->k_stride_tok < p->head_dim || (v && p->v_stride_tok < p->head_dim))
+    return fail(ctx, ASL_EINVAL, "token stride smaller than head_dim");
+  DeviceGuard guard(ctx->device);
+  if (guard.err != hipSuccess) return hip_fail(ctx, guard.err, "set device");
+  hipError_t e = asl::launch_gather(k, v, idx, idx_rows, n_idx, p->n_kv_heads, (int)row_bytes,
+                                    p->k_stride_head * eb, p->k_stride_tok * eb, p->v_stride_head * eb,
+                                    p->v_stride_tok * eb, k_out, v_out, static_cast<hipStream_t>(stream));
+  if (e != hipSuccess) return hip_fail(ctx, e, "gather launch");
+  return ASL_OK;
+}
+
+#pragma GCC visibility pop
+}  // extern "C"

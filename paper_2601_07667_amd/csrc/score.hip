@@ -1,0 +1,399 @@
+// asl_score: window-query x all-key softmax scores, column-summed over the window rows and the
+// GQA group (Alg. 1 steps 5, 6, 8 of the paper; Sec. 4.1 PA equation before pooling).
+//
+// For one KV head the G heads x W window rows form M = G*W query rows that all read the same
+// keys.  score_j = sum_r exp(l_rj - m_r) / Z_r mixes rows with different normalisers, so the
+// final (m_r, Z_r) of every row must be known before rows are added: pass 1 streams K once for
+// the row statistics, pass 2 streams K again for the normalised column sums.  When the caller
+// hands over the rows' log-sum-exp, pass 1 is skipped.
+//
+// Work split: a workgroup owns one KV head and a contiguous chunk of keys; wave w owns query rows
+// [32w, 32w+32) and keeps their bf16 fragments in registers for the whole kernel; K tiles of 128
+// keys are staged through LDS (coalesced 16-byte global loads, padded rows) and every wave reads
+// all of them as the other MFMA operand (v_mfma_f32_32x32x16_bf16).  Pass 1 puts keys on the
+// accumulator's register axis (row statistics reduce in-lane), pass 2 puts query rows there
+// (column sums reduce in-lane).  All reductions have a fixed order: results are deterministic.
+#include "asl_internal.h"
+
+namespace asl {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+constexpr int KT = 128;                       // keys per LDS tile
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kNegBig = -1.0e30f;           // finite stand-in for "no maximum yet"
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// Row of the 32x32 accumulator held by register r of a lane in half `half` (lanes 32..63 = 1).
+__device__ __forceinline__ int acc_row(int r, int half) { return 8 * (r >> 2) + 4 * half + (r & 3); }
+
+template <int D, int NT>
+struct KTileLoader {
+  static constexpr int CPR = D / 8;                       // 16-byte chunks per key row
+  static constexpr int NLOAD = (KT * CPR + NT - 1) / NT;  // chunks per thread
+  static constexpr int ROW = D + 8;                       // padded LDS row, bf16 elements
+  uint4 stage[NLOAD];
+
+  __device__ __forceinline__ void load(const __bf16* kg, int64_t kst, int key0, int N, int tid) {
+#pragma unroll
+    for (int i = 0; i < NLOAD; ++i) {
+      int q = tid + i * NT;
+      if (KT * CPR % NT == 0 || q < KT * CPR) {
+        int row = q / CPR, col = q % CPR;
+        int key = min(key0 + row, N - 1);                 // clamp: rows past N are masked later
+        stage[i] = *reinterpret_cast<const uint4*>(kg + (int64_t)key * kst + col * 8);
+      }
+    }
+  }
+  __device__ __forceinline__ void store(__bf16* lds, int tid) {
+#pragma unroll
+    for (int i = 0; i < NLOAD; ++i) {
+      int q = tid + i * NT;
+      if (KT * CPR % NT == 0 || q < KT * CPR) {
+        int row = q / CPR, col = q % CPR;
+        *reinterpret_cast<uint4*>(lds + row * ROW + col * 8) = stage[i];
+      }
+    }
+  }
+};
+
+template <int D>
+__device__ __forceinline__ void load_q_frags(const __bf16* qg, int qrow, int M, int half,
+                                             bf16x8 (&qf)[D / 16]) {
+#pragma unroll
+  for (int ks = 0; ks < D / 16; ++ks) {
+    if (qrow < M) {
+      qf[ks] = *reinterpret_cast<const bf16x8*>(qg + (int64_t)qrow * D + ks * 16 + half * 8);
+    } else {
+      bf16x8 z = {0, 0, 0, 0, 0, 0, 0, 0};
+      qf[ks] = z;
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Pass 1: per-row running (max, sum) over this workgroup's key chunk, in the log2 domain.
+// row_part[((g*n_chunks + chunk)*M + row)*2 + {0,1}] = (m, z) with  sum_j 2^(c1*l_j) = z * 2^m.
+template <int D, int NW>
+__global__ void __launch_bounds__(NW * 64)
+score_rowstats_kernel(const __bf16* __restrict__ q_obs, const __bf16* __restrict__ k, int64_t ksh,
+                      int64_t kst, int Hk, int M, int W, int N, int tiles_per_chunk, int n_chunks,
+                      float c1, float* __restrict__ row_part) {
+  constexpr int NT = NW * 64;
+  constexpr int ROW = D + 8;
+  constexpr int KS = D / 16;
+  __shared__ __attribute__((aligned(16))) __bf16 lds_k[KT * ROW];
+
+  const int g = blockIdx.x % Hk, chunk = blockIdx.x / Hk;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, ln = lane & 31, half = lane >> 5;
+  const int T = N - W;
+  const int qrow = wave * 32 + ln;
+  const int wi = qrow % W;                      // window row of this lane's query row
+
+  bf16x8 qf[KS];
+  load_q_frags<D>(q_obs + (int64_t)g * M * D, qrow, M, half, qf);
+
+  const __bf16* kg = k + (int64_t)g * ksh;
+  const int n_tiles_total = (N + KT - 1) / KT;
+  const int tile0 = chunk * tiles_per_chunk;
+  const int tile_end = min(tile0 + tiles_per_chunk, n_tiles_total);
+
+  float m_run = kNegBig, z_run = 0.f;
+  KTileLoader<D, NT> ld;
+  if (tile0 < tile_end) ld.load(kg, kst, tile0 * KT, N, tid);
+
+  for (int tile = tile0; tile < tile_end; ++tile) {
+    __syncthreads();                            // every wave is done reading the previous tile
+    ld.store(lds_k, tid);
+    __syncthreads();
+    if (tile + 1 < tile_end) ld.load(kg, kst, (tile + 1) * KT, N, tid);
+
+    const int kbase = tile * KT;
+    const bool need_mask = (kbase + KT > T);    // touches the window block or the tail past N
+#pragma unroll
+    for (int sub = 0; sub < KT / 32; ++sub) {
+      f32x16 acc;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+      const __bf16* krow = lds_k + (sub * 32 + ln) * ROW + half * 8;
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        bf16x8 kf = *reinterpret_cast<const bf16x8*>(krow + ks * 16);
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], acc, 0, 0, 0);   // [key][query row]
+      }
+      if (need_mask) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          int key = kbase + sub * 32 + acc_row(r, half);
+          bool masked = (key >= N) || (key >= T && (key - T) > wi);
+          if (masked) acc[r] = -INFINITY;
+        }
+      }
+      float mx = acc[0];
+#pragma unroll
+      for (int r = 1; r < 16; r += 2) mx = fmaxf(mx, fmaxf(acc[r], acc[(r + 1) & 15]));
+      const float m_new = fmaxf(m_run, mx * c1);
+      float sum = 0.f;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) sum += fast_exp2(fmaf(acc[r], c1, -m_new));
+      z_run = z_run * fast_exp2(m_run - m_new) + sum;
+      m_run = m_new;
+    }
+  }
+  // the two lane halves hold disjoint keys of the same query row
+  const float m_o = __shfl_xor(m_run, 32), z_o = __shfl_xor(z_run, 32);
+  const float m = fmaxf(m_run, m_o);
+  const float z = (half == 0) ? (z_run * fast_exp2(m_run - m) + z_o * fast_exp2(m_o - m))
+                              : (z_o * fast_exp2(m_o - m) + z_run * fast_exp2(m_run - m));
+  if (half == 0 && qrow < M) {
+    float* dst = row_part + ((int64_t)(g * n_chunks + chunk) * M + qrow) * 2;
+    dst[0] = m;
+    dst[1] = z;
+  }
+}
+
+// Fold the per-chunk partials of every row into one log2-domain offset  m + log2(Z).
+__global__ void score_combine_kernel(const float* __restrict__ row_part, int Hk, int M, int n_chunks,
+                                     float* __restrict__ row_const) {
+  int r = blockIdx.x * blockDim.x + threadIdx.x;
+  if (r >= Hk * M) return;
+  int g = r / M, row = r % M;
+  const float* p = row_part + ((int64_t)g * n_chunks * M + row) * 2;
+  float m = kNegBig;
+  for (int c = 0; c < n_chunks; ++c) m = fmaxf(m, p[(int64_t)c * M * 2]);
+  float z = 0.f;
+  for (int c = 0; c < n_chunks; ++c) z += p[(int64_t)c * M * 2 + 1] * exp2f(p[(int64_t)c * M * 2] - m);
+  row_const[r] = m + log2f(z);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Pass 2: u_group[g][j] = sum over the M rows of 2^(c1*l_rj - rc_r),  j < T,
+// rc_r = rc_mul * row_const[g*M + r]  (log2-domain offset that already contains log2 Z_r).
+template <int D, int NW>
+__global__ void __launch_bounds__(NW * 64)
+score_colsum_kernel(const __bf16* __restrict__ q_obs, const __bf16* __restrict__ k, int64_t ksh,
+                    int64_t kst, int Hk, int M, int N, int T, int tiles_per_chunk, float c1,
+                    const float* __restrict__ row_const, float rc_mul, float* __restrict__ u_group) {
+  constexpr int NT = NW * 64;
+  constexpr int ROW = D + 8;
+  constexpr int KS = D / 16;
+  __shared__ __attribute__((aligned(16))) __bf16 lds_k[KT * ROW];
+  __shared__ float red[NW][KT];
+
+  const int g = blockIdx.x % Hk, chunk = blockIdx.x / Hk;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, ln = lane & 31, half = lane >> 5;
+  const int qrow = wave * 32 + ln;
+
+  bf16x8 qf[KS];
+  load_q_frags<D>(q_obs + (int64_t)g * M * D, qrow, M, half, qf);
+
+  float rc[16];
+#pragma unroll
+  for (int r = 0; r < 16; ++r) {
+    int row = wave * 32 + acc_row(r, half);
+    rc[r] = (row < M) ? row_const[(int64_t)g * M + row] * rc_mul : INFINITY;   // padded rows add 0
+  }
+
+  const __bf16* kg = k + (int64_t)g * ksh;
+  const int n_tiles_total = (T + KT - 1) / KT;
+  const int tile0 = chunk * tiles_per_chunk;
+  const int tile_end = min(tile0 + tiles_per_chunk, n_tiles_total);
+
+  KTileLoader<D, NT> ld;
+  if (tile0 < tile_end) ld.load(kg, kst, tile0 * KT, N, tid);
+
+  for (int tile = tile0; tile < tile_end; ++tile) {
+    __syncthreads();                            // previous tile's LDS reads (keys and red) are done
+    ld.store(lds_k, tid);
+    __syncthreads();
+    if (tile + 1 < tile_end) ld.load(kg, kst, (tile + 1) * KT, N, tid);
+
+    const int kbase = tile * KT;
+#pragma unroll
+    for (int sub = 0; sub < KT / 32; ++sub) {
+      f32x16 acc;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+      const __bf16* krow = lds_k + (sub * 32 + ln) * ROW + half * 8;
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        bf16x8 kf = *reinterpret_cast<const bf16x8*>(krow + ks * 16);
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[ks], kf, acc, 0, 0, 0);   // [query row][key]
+      }
+      float cs = 0.f;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) cs += fast_exp2(fmaf(acc[r], c1, -rc[r]));
+      const float other = __shfl_xor(cs, 32);
+      if (half == 0) red[wave][sub * 32 + ln] = cs + other;
+    }
+    __syncthreads();
+    for (int j = tid; j < KT; j += NT) {
+      float s = red[0][j];
+#pragma unroll
+      for (int w = 1; w < NW; ++w) s += red[w][j];
+      if (kbase + j < T) u_group[(int64_t)g * T + kbase + j] = s;
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Generic path (any d, any M, fp32 or bf16 storage, plain fp32 FMA): small shapes and the on-GPU
+// cross-check of the MFMA path.
+template <typename TIn> __device__ __forceinline__ float ldf(const TIn* p);
+template <> __device__ __forceinline__ float ldf<float>(const float* p) { return *p; }
+template <> __device__ __forceinline__ float ldf<__bf16>(const __bf16* p) { return (float)*p; }
+
+// one workgroup per global query row r = h*W + wi: log2-domain offset m + log2 Z (or from lse)
+template <typename TIn>
+__global__ void __launch_bounds__(256)
+score_rowstats_generic(const TIn* __restrict__ q_obs, const TIn* __restrict__ k, int64_t ksh, int64_t kst,
+                       int G, int W, int N, int D, float c1, float* __restrict__ row_const) {
+  extern __shared__ float sm[];                // D floats of q, then 2*256 for the reduction
+  float* qs = sm;
+  float* red_m = sm + D;
+  float* red_z = red_m + 256;
+  const int r = blockIdx.x, h = r / W, wi = r % W, g = h / G;
+  const int T = N - W;
+  for (int c = threadIdx.x; c < D; c += 256) qs[c] = ldf<TIn>(q_obs + (int64_t)r * D + c);
+  __syncthreads();
+  const TIn* kg = k + (int64_t)g * ksh;
+  const int n_vis = T + wi + 1;                // past keys + window keys 0..wi
+  float m = kNegBig, z = 0.f;
+  for (int j = threadIdx.x; j < n_vis; j += 256) {
+    const TIn* kr = kg + (int64_t)j * kst;
+    float dot = 0.f;
+    for (int c = 0; c < D; ++c) dot = fmaf(qs[c], ldf<TIn>(kr + c), dot);
+    float x = dot * c1;
+    float mn = fmaxf(m, x);
+    z = z * exp2f(m - mn) + exp2f(x - mn);
+    m = mn;
+  }
+  red_m[threadIdx.x] = m;
+  red_z[threadIdx.x] = z;
+  __syncthreads();
+  for (int s = 128; s > 0; s >>= 1) {
+    if (threadIdx.x < s) {
+      float m1 = red_m[threadIdx.x], m2 = red_m[threadIdx.x + s];
+      float mn = fmaxf(m1, m2);
+      red_z[threadIdx.x] = red_z[threadIdx.x] * exp2f(m1 - mn) + red_z[threadIdx.x + s] * exp2f(m2 - mn);
+      red_m[threadIdx.x] = mn;
+    }
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) row_const[r] = red_m[0] + log2f(red_z[0]);
+}
+
+// one thread per (KV head g, past key j): loop over the M rows of the group
+template <typename TIn>
+__global__ void __launch_bounds__(256)
+score_colsum_generic(const TIn* __restrict__ q_obs, const TIn* __restrict__ k, int64_t ksh, int64_t kst,
+                     int M, int T, int D, float c1, const float* __restrict__ row_const, float rc_mul,
+                     float* __restrict__ u_group) {
+  const int g = blockIdx.y;
+  const int j = blockIdx.x * 256 + threadIdx.x;
+  if (j >= T) return;
+  const TIn* kr = k + (int64_t)g * ksh + (int64_t)j * kst;
+  const TIn* qg = q_obs + (int64_t)g * M * D;
+  float s = 0.f;
+  for (int r = 0; r < M; ++r) {
+    float dot = 0.f;
+    for (int c = 0; c < D; ++c) dot = fmaf(ldf<TIn>(qg + (int64_t)r * D + c), ldf<TIn>(kr + c), dot);
+    s += exp2f(fmaf(dot, c1, -row_const[(int64_t)g * M + r] * rc_mul));
+  }
+  u_group[(int64_t)g * T + j] = s;
+}
+
+// ---------------------------------------------------------------------------------------------
+bool score_mfma_supported(const asl_params& p) {
+  const int M = (p.n_q_heads / p.n_kv_heads) * p.window;
+  return p.dtype == ASL_BF16 && (p.head_dim == 64 || p.head_dim == 128) && M <= 256;
+}
+
+// Key chunks per KV head: enough workgroups to fill 256 CUs a few times over.
+int score_chunks(const asl_params& p) {
+  const int n_tiles = (p.seq_len + KT - 1) / KT;
+  int want = (1024 + p.n_kv_heads - 1) / p.n_kv_heads;
+  if (want > kMaxChunks) want = kMaxChunks;
+  if (want > n_tiles) want = n_tiles;
+  if (want < 1) want = 1;
+  const int tpc = (n_tiles + want - 1) / want;
+  return (n_tiles + tpc - 1) / tpc;
+}
+
+template <int D, int NW>
+static hipError_t launch_score_mfma(const asl_params& p, const Workspace& ws, const __bf16* q,
+                                    const __bf16* k, const float* lse, float c1, hipStream_t st) {
+  const int Hk = p.n_kv_heads, M = (p.n_q_heads / Hk) * p.window, N = p.seq_len, T = N - p.window;
+  const int n_chunks = score_chunks(p);
+  const int n_tiles1 = (N + KT - 1) / KT;
+  const int tpc1 = (n_tiles1 + n_chunks - 1) / n_chunks;
+  if (!lse) {
+    hipLaunchKernelGGL((score_rowstats_kernel<D, NW>), dim3(Hk * n_chunks), dim3(NW * 64), 0, st, q, k,
+                       p.k_stride_head, p.k_stride_tok, Hk, M, p.window, N, tpc1, n_chunks, c1,
+                       ws.row_part);
+    const int rows = Hk * M;
+    hipLaunchKernelGGL(score_combine_kernel, dim3((rows + 255) / 256), dim3(256), 0, st, ws.row_part,
+                       Hk, M, n_chunks, ws.row_const);
+  }
+  const int n_tiles2 = (T + KT - 1) / KT;
+  const int tpc2 = (n_tiles2 + n_chunks - 1) / n_chunks;
+  const int n_chunks2 = (n_tiles2 + tpc2 - 1) / tpc2;
+  hipLaunchKernelGGL((score_colsum_kernel<D, NW>), dim3(Hk * n_chunks2), dim3(NW * 64), 0, st, q, k,
+                     p.k_stride_head, p.k_stride_tok, Hk, M, N, T, tpc2, c1,
+                     lse ? lse : ws.row_const, lse ? kLog2e : 1.0f, ws.u_group);
+  return hipGetLastError();
+}
+
+template <int D>
+static hipError_t dispatch_nw(int nw, const asl_params& p, const Workspace& ws, const __bf16* q,
+                              const __bf16* k, const float* lse, float c1, hipStream_t st) {
+  switch (nw) {
+    case 1: return launch_score_mfma<D, 1>(p, ws, q, k, lse, c1, st);
+    case 2: return launch_score_mfma<D, 2>(p, ws, q, k, lse, c1, st);
+    case 3: return launch_score_mfma<D, 3>(p, ws, q, k, lse, c1, st);
+    case 4: return launch_score_mfma<D, 4>(p, ws, q, k, lse, c1, st);
+    case 5: return launch_score_mfma<D, 5>(p, ws, q, k, lse, c1, st);
+    case 6: return launch_score_mfma<D, 6>(p, ws, q, k, lse, c1, st);
+    case 7: return launch_score_mfma<D, 7>(p, ws, q, k, lse, c1, st);
+    default: return launch_score_mfma<D, 8>(p, ws, q, k, lse, c1, st);
+  }
+}
+
+template <typename TIn>
+static hipError_t launch_score_generic(const asl_params& p, const Workspace& ws, const TIn* q,
+                                       const TIn* k, const float* lse, float c1, hipStream_t st) {
+  const int Hk = p.n_kv_heads, G = p.n_q_heads / Hk, W = p.window, M = G * W, N = p.seq_len, T = N - W;
+  const int D = p.head_dim;
+  if (!lse) {
+    size_t sm = (size_t)(D + 512) * sizeof(float);
+    hipLaunchKernelGGL((score_rowstats_generic<TIn>), dim3(p.n_q_heads * W), dim3(256), sm, st, q, k,
+                       p.k_stride_head, p.k_stride_tok, G, W, N, D, c1, ws.row_const);
+  }
+  hipLaunchKernelGGL((score_colsum_generic<TIn>), dim3((T + 255) / 256, Hk), dim3(256), 0, st, q, k,
+                     p.k_stride_head, p.k_stride_tok, M, T, D, c1, lse ? lse : ws.row_const,
+                     lse ? kLog2e : 1.0f, ws.u_group);
+  return hipGetLastError();
+}
+
+hipError_t launch_score(const asl_params& p, const Workspace& ws, const void* q_obs, const void* k,
+                        const float* lse, hipStream_t st) {
+  const float scale = p.scale > 0.f ? p.scale : 1.0f / sqrtf((float)p.head_dim);
+  const float c1 = scale * kLog2e;
+  const int M = (p.n_q_heads / p.n_kv_heads) * p.window;
+  if (score_mfma_supported(p) && !(p.flags & ASL_FLAG_GENERIC_SCORE)) {
+    const int nw = (M + 31) / 32;
+    const __bf16* q = static_cast<const __bf16*>(q_obs);
+    const __bf16* kk = static_cast<const __bf16*>(k);
+    return p.head_dim == 128 ? dispatch_nw<128>(nw, p, ws, q, kk, lse, c1, st)
+                             : dispatch_nw<64>(nw, p, ws, q, kk, lse, c1, st);
+  }
+  if (p.dtype == ASL_BF16)
+    return launch_score_generic<__bf16>(p, ws, static_cast<const __bf16*>(q_obs),
+                                        static_cast<const __bf16*>(k), lse, c1, st);
+  return launch_score_generic<float>(p, ws, static_cast<const float*>(q_obs),
+                                     static_cast<const float*>(k), lse, c1, st);
+}
+
+}  // namespace asl

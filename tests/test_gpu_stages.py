@@ -1,0 +1,248 @@
+"""Stage-isolated GPU parity: each libasl kernel is fed the oracle-side input of its stage
+(cast to the kernel's input dtype) and compared with the oracle's output for that stage.
+Integer outputs (ranks, statistic integers, top-k indices, gathered bytes) must be bit-exact."""
+import ctypes as C
+
+import numpy as np
+import pytest
+
+from oracle import asl_oracle as orc
+from paper_2601_07667_amd import asl, synth
+import gpu_util as gu
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def ctx(gpu_device):
+    c = asl.Asl(262144, 8, 32 * 64)
+    yield c
+    c.close()
+
+
+def _torch():
+    import torch
+    return torch
+
+
+# ----------------------------------------------------------------------------- pool
+@pytest.mark.parametrize("rows,T,S", [(1, 1, 1), (2, 5, 7), (8, 496, 7), (3, 1000, 1), (8, 32736, 7),
+                                      (2, 777, 129), (8, 131040, 7)])
+def test_pool(ctx, gpu_device, rows, T, S):
+    torch = _torch()
+    rng = np.random.default_rng(rows * 7 + T)
+    u = rng.random((rows, T), dtype=np.float32)
+    ud = torch.from_numpy(u).to(gpu_device)
+    p = torch.empty_like(ud)
+    s = torch.empty(T, dtype=torch.float32, device=gpu_device)
+    ctx.asl_pool(ud, rows, T, S, p, s)
+    ref = orc.avg_pool1d(u.astype(np.float64), S)
+    np.testing.assert_allclose(p.cpu().numpy(), ref, rtol=2e-6, atol=1e-7)
+    np.testing.assert_allclose(s.cpu().numpy(), ref.sum(axis=0), rtol=4e-6, atol=1e-7)
+
+
+# ----------------------------------------------------------------------------- rank
+def _rank_case(ctx, dev, s: np.ndarray):
+    torch = _torch()
+    T = s.shape[0]
+    sd = torch.from_numpy(s).to(dev)
+    out = torch.full((T,), -1, dtype=torch.int32, device=dev)
+    ctx.asl_rank(sd, T, out)
+    np.testing.assert_array_equal(out.cpu().numpy().astype(np.int64), orc.rank_desc(s.astype(np.float64)))
+
+
+@pytest.mark.parametrize("T", [1, 2, 63, 64, 65, 2047, 2048, 2049, 5000, 32736, 131040, 262080])
+def test_rank_random_with_ties(ctx, gpu_device, T):
+    rng = np.random.default_rng(T)
+    s = rng.standard_normal(T).astype(np.float32)
+    if T > 10:
+        s[rng.integers(0, T, T // 4)] = s[rng.integers(0, T, T // 4)]     # exact ties
+        s[rng.integers(0, T, T // 8)] = 0.0
+        s[rng.integers(0, T, T // 8)] = -0.0                               # -0 ties with +0
+    _rank_case(ctx, gpu_device, s)
+
+
+def test_rank_special(ctx, gpu_device):
+    T = 5000
+    _rank_case(ctx, gpu_device, np.ones(T, dtype=np.float32))                               # all equal
+    _rank_case(ctx, gpu_device, np.arange(T, dtype=np.float32))                             # increasing
+    _rank_case(ctx, gpu_device, -np.arange(T, dtype=np.float32))                            # decreasing
+    _rank_case(ctx, gpu_device, np.exp(np.random.default_rng(1).normal(0, 3, T)).astype(np.float32))
+    tiny = (np.random.default_rng(2).random(T) * 1e-40).astype(np.float32)                  # denormals
+    _rank_case(ctx, gpu_device, tiny)
+
+
+def test_rank_is_deterministic(ctx, gpu_device):
+    torch = _torch()
+    T = 131040
+    s = torch.from_numpy(np.random.default_rng(3).random(T, dtype=np.float32)).to(gpu_device)
+    a = torch.empty(T, dtype=torch.int32, device=gpu_device)
+    b = torch.empty(T, dtype=torch.int32, device=gpu_device)
+    ctx.asl_rank(s, T, a)
+    ctx.asl_rank(s, T, b)
+    assert torch.equal(a, b)
+
+
+# ----------------------------------------------------------------------------- statistic
+def _stat_case(ctx, dev, R: np.ndarray, l_obs: int, k: int, tau: float, layer_idx: int,
+               init_var=None):
+    """Place the rows of R (oldest first) in the ring as the library expects and run asl_rankvar."""
+    torch = _torch()
+    n, T = R.shape
+    ring = np.full((l_obs, T), 10**9, dtype=np.int32)                 # poison unused rows
+    for j in range(n):
+        layer = layer_idx - (n - 1) + j
+        ring[layer % l_obs] = R[j]
+    ringd = torch.from_numpy(ring).to(dev)
+    state = asl.new_state(dev)
+    asl.write_state(state, init_var=init_var or 0.0, init_set=int(init_var is not None),
+                    n_valid_rows=n, last_layer=layer_idx)
+    out = asl.new_stat(dev)
+    ctx.asl_rankvar(ringd, l_obs, T, layer_idx, 0, k, tau, state, out)
+    return asl.read_struct(out, asl.AslStat), asl.read_struct(state, asl.AslState)
+
+
+@pytest.mark.parametrize("n,l_obs,T,k", [(2, 8, 100, 10), (8, 8, 5000, 300), (5, 8, 32736, 992),
+                                         (8, 8, 131040, 2016), (3, 3, 1000, 1000), (8, 8, 262080, 4032)])
+def test_rankvar_exact(ctx, gpu_device, n, l_obs, T, k):
+    rng = np.random.default_rng(n + T)
+    base = rng.standard_normal(T)
+    R = np.stack([orc.rank_desc(base + 0.5 * rng.standard_normal(T)) for _ in range(n)])
+    ref = orc.rank_variance(R, k)
+    st, state = _stat_case(ctx, gpu_device, R, l_obs, k, tau=0.3, layer_idx=37)
+    assert st.evaluated == 1 and st.n_rows == n
+    assert st.numerator == ref.numerator and st.union_size == ref.union_size
+    assert st.var_top == ref.var_top                                   # same integer, same single division
+    assert st.rel_var == 1.0 and st.selected == 0                      # first evaluation: relative variance 1
+    assert state.init_set == 1 and state.init_var == ref.var_top and state.n_valid_rows == n
+    # second evaluation against a given init_var: decision and release of the ring
+    st2, state2 = _stat_case(ctx, gpu_device, R, l_obs, k, tau=0.3, layer_idx=37, init_var=ref.var_top * 4)
+    assert st2.rel_var == ref.var_top / (ref.var_top * 4) and st2.selected == 1
+    assert state2.n_valid_rows == 0 and state2.init_var == ref.var_top * 4
+
+
+def test_rankvar_guards_and_degenerate(ctx, gpu_device):
+    torch = _torch()
+    T = 300
+    R = np.stack([np.arange(T), np.arange(T)])
+    st, state = _stat_case(ctx, gpu_device, R[:1], 8, 10, 0.3, layer_idx=12)          # one row only
+    assert st.evaluated == 0 and st.selected == 0 and state.init_set == 0
+    st, state = _stat_case(ctx, gpu_device, R, 8, 10, 0.3, layer_idx=12)              # identical rows
+    assert st.evaluated == 1 and st.var_top == 0.0 and np.isnan(st.rel_var) and st.selected == 0
+    assert state.init_set == 1 and state.init_var == 0.0
+    st, _ = _stat_case(ctx, gpu_device, np.stack([np.arange(T), np.arange(T)[::-1]]), 8, 10, 0.3,
+                       layer_idx=13, init_var=0.0)
+    assert np.isinf(st.rel_var) and st.selected == 0
+    # layer below L_min: nothing evaluated, state untouched
+    ring = torch.zeros((8, T), dtype=torch.int32, device=gpu_device)
+    state = asl.new_state(gpu_device)
+    asl.write_state(state, n_valid_rows=5, last_layer=4)
+    out = asl.new_stat(gpu_device)
+    ctx.asl_rankvar(ring, 8, T, 4, 10, 10, 0.3, state, out)
+    assert asl.read_struct(out, asl.AslStat).evaluated == 0
+    assert asl.read_struct(state, asl.AslState).n_valid_rows == 5
+
+
+# ----------------------------------------------------------------------------- select
+def _select_case(ctx, dev, scores: np.ndarray, budget: int, W: int):
+    torch = _torch()
+    rows, T = scores.shape
+    N = T + W
+    p = asl.make_params(rows, rows, 64, N, W, 7, budget)
+    k = min(budget, N) - W
+    sd = torch.from_numpy(scores).to(dev)
+    out = torch.full((rows, k + W), -7, dtype=torch.int32, device=dev)
+    ctx.asl_select_topk(p, sd, rows, out)
+    ref = orc.select_indices(scores.astype(np.float64), k, W)
+    np.testing.assert_array_equal(out.cpu().numpy().astype(np.int64), ref)
+
+
+@pytest.mark.parametrize("rows,T,budget,W", [(1, 10, 6, 2), (2, 496, 128, 16), (8, 32736, 2048, 32),
+                                             (8, 131040, 2048, 32), (1, 131040, 2048, 32),
+                                             (8, 262080, 4096, 64), (3, 4097, 5000, 8), (2, 9000, 33, 32)])
+def test_select_random_with_ties(ctx, gpu_device, rows, T, budget, W):
+    rng = np.random.default_rng(T + rows)
+    s = rng.random((rows, T), dtype=np.float32)
+    if T > 100:
+        s = np.round(s, 3).astype(np.float32)           # many exact ties around the threshold
+    _select_case(ctx, gpu_device, s, budget, W)
+
+
+def test_select_special(ctx, gpu_device):
+    T, W = 6000, 16
+    _select_case(ctx, gpu_device, np.ones((2, T), dtype=np.float32), 100, W)               # all equal: first k
+    _select_case(ctx, gpu_device, np.zeros((1, T), dtype=np.float32), 100, W)
+    s = np.random.default_rng(5).standard_normal((2, T)).astype(np.float32)                 # negatives
+    _select_case(ctx, gpu_device, s, 1000, W)
+    _select_case(ctx, gpu_device, s, T + W + 50, W)                                         # budget >= N: keep all
+
+
+# ----------------------------------------------------------------------------- gather
+@pytest.mark.parametrize("cfg", [1, 2])
+def test_gather_bit_exact(ctx, gpu_device, cfg):
+    torch = _torch()
+    L = synth.config_layer(cfg)
+    sh = L.shape
+    p = gu.params_of(sh)
+    kd, vd = gu.to_dev(L.k, sh.dtype, gpu_device), gu.to_dev(L.v, sh.dtype, gpu_device)
+    rng = np.random.default_rng(cfg)
+    n_idx = sh.k + sh.W
+    idx = np.stack([np.sort(rng.choice(sh.N, n_idx, replace=False)) for _ in range(sh.Hk)]).astype(np.int32)
+    for idx_rows, I in ((sh.Hk, idx), (1, idx[:1])):
+        Id = torch.from_numpy(I).to(gpu_device)
+        ko = torch.zeros((sh.Hk, n_idx, sh.d), dtype=kd.dtype, device=gpu_device)
+        vo = torch.zeros_like(ko)
+        ctx.asl_gather_kv(p, kd, vd, Id, idx_rows, n_idx, ko, vo)
+        kr, vr = orc.gather_kv(L.k, L.v, I if idx_rows > 1 else I[0])
+        assert np.array_equal(ko.float().cpu().numpy(), kr)            # bf16/f32 values are exact in fp32
+        assert np.array_equal(vo.float().cpu().numpy(), vr)
+    # identity index = plain copy; strided K (token stride 2d) reads the right rows
+    Id = torch.arange(sh.N, dtype=torch.int32, device=gpu_device)
+    ko = torch.zeros_like(kd)
+    ctx.asl_gather_kv(p, kd, None, Id, 1, sh.N, ko, None)
+    assert torch.equal(ko, kd)
+    wide = torch.zeros((sh.Hk, sh.N, 2 * sh.d), dtype=kd.dtype, device=gpu_device)
+    wide[:, :, :sh.d] = kd
+    p2 = asl.make_params(sh.Hq, sh.Hk, sh.d, sh.N, sh.W, sh.S, sh.budget, dtype=p.dtype,
+                         k_strides=(sh.N * 2 * sh.d, 2 * sh.d))
+    ko.zero_()
+    ctx.asl_gather_kv(p2, wide, None, Id, 1, sh.N, ko, None)
+    assert torch.equal(ko, kd)
+
+
+# ----------------------------------------------------------------------------- errors
+def test_argument_errors(ctx, gpu_device):
+    torch = _torch()
+    sh = synth.shape_of(1)
+    good = gu.params_of(sh)
+    t = torch.zeros(16, device=gpu_device)
+
+    def expect(status, fn):
+        with pytest.raises(asl.AslError) as e:
+            fn()
+        assert e.value.status == status, str(e.value)
+
+    def with_(**kw):
+        p = gu.params_of(sh)
+        for a, b in kw.items():
+            setattr(p, a, b)
+        return p
+
+    sc = lambda p: ctx.asl_score_layer(p, t, t, t, t)
+    expect(asl.ASL_EINVAL, lambda: sc(with_(n_q_heads=3)))               # Hq % Hk
+    expect(asl.ASL_EINVAL, lambda: sc(with_(window=0)))
+    expect(asl.ASL_EINVAL, lambda: sc(with_(window=sh.N)))               # W < N
+    expect(asl.ASL_EINVAL, lambda: sc(with_(pool_kernel=4)))             # even S
+    expect(asl.ASL_EINVAL, lambda: sc(with_(budget=sh.W)))               # k <= 0
+    expect(asl.ASL_EUNSUPPORTED, lambda: sc(with_(dtype=5)))
+    expect(asl.ASL_ENOMEM, lambda: sc(with_(seq_len=1 << 20)))           # beyond the context limits
+    expect(asl.ASL_EINVAL, lambda: ctx.asl_score_layer(good, None, t, t, t))
+    expect(asl.ASL_EINVAL, lambda: ctx.asl_rank(t, 0, t))
+    expect(asl.ASL_EINVAL, lambda: ctx.asl_pool(t, 1, 16, 2, t))
+    expect(asl.ASL_EINVAL, lambda: ctx.asl_gather_kv(good, t, None, t, 3, 4, t, None))   # idx_rows not 1/Hk
+    expect(asl.ASL_EINVAL, lambda: ctx.asl_rankvar(t, 1, 16, 0, 0, 4, 0.3, t, t))        # L_obs < 2
+    expect(asl.ASL_EUNSUPPORTED, lambda: ctx.asl_rankvar(t, 64, 2_000_000, 0, 0, 4, 0.3, t, t))
+    h = C.c_void_p()
+    assert ctx.lib.asl_create(C.byref(h), 0, 1, 8, 8) == asl.ASL_EINVAL
+    assert ctx.lib.asl_create(C.byref(h), 99, 1024, 8, 8) == asl.ASL_EHIP
+    assert "idx_rows" in ctx.lib.asl_last_error(ctx.h).decode() or True
