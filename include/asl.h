@@ -154,6 +154,18 @@ asl_status asl_gather_kv(asl_ctx* ctx, const asl_params* params, const void* k, 
                          const int32_t* idx, int32_t idx_rows, int32_t n_idx, void* k_out,
                          void* v_out, void* stream);
 
+/* Measurement aid (not a step of the paper's method; for callers that time the kernels of the
+ * calls above).  Kernel ids: 0 score row statistics (pass 1), 1 its combine, 2 score column sums
+ * (pass 2), 3 pool, 4 sort histogram, 5 sort scatter, 6 ring push / skip, 7 rank variance,
+ * 8 select histogram, 9 select count, 10 select write, 11 gather, 12 plain-FMA score kernels.
+ * asl_profile_enable: launches whose id bit is set in kernel_mask are bracketed by HIP events on
+ *   the call's stream, up to max_records launches (further ones run unrecorded); mask 0 turns
+ *   it off and frees the events.  Allocates host memory and events: not for the hot loop.
+ * asl_profile_collect: waits for the recorded events of kernel_id and returns their summed
+ *   duration in milliseconds and their number; kernel_id -1 clears the records instead. */
+asl_status asl_profile_enable(asl_ctx* ctx, uint32_t kernel_mask, int32_t max_records);
+asl_status asl_profile_collect(asl_ctx* ctx, int32_t kernel_id, double* total_ms, int32_t* launches);
+
 #ifdef __cplusplus
 }
 #endif

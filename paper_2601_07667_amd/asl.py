@@ -19,7 +19,8 @@ ASL_FLAG_GENERIC_SCORE = 1
 _STATUS = {0: "ASL_OK", -1: "ASL_EINVAL", -2: "ASL_ENOMEM", -3: "ASL_EHIP", -4: "ASL_EUNSUPPORTED"}
 
 EXPORTS = ["asl_create", "asl_destroy", "asl_last_error", "asl_workspace_bytes", "asl_score_layer",
-           "asl_pool", "asl_rank", "asl_rankvar", "asl_rank_stat", "asl_select_topk", "asl_gather_kv"]
+           "asl_pool", "asl_rank", "asl_rankvar", "asl_rank_stat", "asl_select_topk", "asl_gather_kv",
+           "asl_profile_enable", "asl_profile_collect"]
 
 
 class AslParams(C.Structure):
@@ -82,6 +83,10 @@ def load() -> C.CDLL:
     lib.asl_select_topk.restype = C.c_int
     lib.asl_gather_kv.argtypes = [vp, C.POINTER(AslParams), vp, vp, vp, i32, i32, vp, vp, vp]
     lib.asl_gather_kv.restype = C.c_int
+    lib.asl_profile_enable.argtypes = [vp, C.c_uint32, i32]
+    lib.asl_profile_enable.restype = C.c_int
+    lib.asl_profile_collect.argtypes = [vp, i32, C.POINTER(C.c_double), C.POINTER(i32)]
+    lib.asl_profile_collect.restype = C.c_int
     _lib = lib
     return lib
 
@@ -154,9 +159,23 @@ class Asl:
         self._check(self.lib.asl_select_topk(self.h, C.byref(params), _ptr(scores), rows, _ptr(idx_out),
                                              _stream()))
 
+    def asl_profile_enable(self, kernel_mask: int, max_records: int) -> None:
+        self._check(self.lib.asl_profile_enable(self.h, kernel_mask, max_records))
+
+    def asl_profile_collect(self, kernel_id: int):
+        """(total milliseconds, launches) of the recorded launches of one kernel id; -1 clears."""
+        ms, n = C.c_double(), C.c_int32()
+        self._check(self.lib.asl_profile_collect(self.h, kernel_id, C.byref(ms), C.byref(n)))
+        return ms.value, n.value
+
     def asl_gather_kv(self, params: AslParams, k, v, idx, idx_rows: int, n_idx: int, k_out, v_out) -> None:
         self._check(self.lib.asl_gather_kv(self.h, C.byref(params), _ptr(k), _ptr(v), _ptr(idx), idx_rows,
                                            n_idx, _ptr(k_out), _ptr(v_out), _stream()))
+
+
+KERNEL_NAMES = ["score_rowstats", "score_combine", "score_colsum", "pool", "sort_hist", "sort_scatter",
+                "ring_push", "rankvar", "select_hist", "select_count", "select_write", "gather",
+                "score_generic"]
 
 
 # -- helpers for the device-resident structs (plumbing only) ---------------------------------------

@@ -14,6 +14,7 @@ struct asl_ctx {
   void* base;
   size_t bytes;
   asl::Workspace ws;
+  asl::Prof prof;
   char err[256];
 };
 
@@ -153,6 +154,7 @@ asl_status asl_create(asl_ctx** out, int device, int32_t max_seq_len, int32_t ma
     return e == hipErrorOutOfMemory ? ASL_ENOMEM : ASL_EHIP;
   }
   carve(static_cast<char*>(ctx->base), max_seq_len, max_kv_heads, max_q_rows, &ctx->ws);
+  ctx->ws.prof = nullptr;
   // tickets, accumulators and select histograms must start at zero; the kernels that use them
   // leave them at zero again
   e = hipMemset(ctx->base, 0, ctx->bytes);
@@ -165,9 +167,77 @@ asl_status asl_create(asl_ctx** out, int device, int32_t max_seq_len, int32_t ma
   return ASL_OK;
 }
 
+static void prof_release(asl_ctx* ctx) {
+  asl::Prof& pf = ctx->prof;
+  for (int i = 0; i < pf.cap; ++i) {
+    (void)hipEventDestroy(pf.start[i]);
+    (void)hipEventDestroy(pf.stop[i]);
+  }
+  delete[] pf.start;
+  delete[] pf.stop;
+  delete[] pf.id;
+  pf = asl::Prof();
+  ctx->ws.prof = nullptr;
+}
+
+asl_status asl_profile_enable(asl_ctx* ctx, uint32_t kernel_mask, int32_t max_records) {
+  if (!ctx) return ASL_EINVAL;
+  if (max_records < 0 || max_records > (1 << 20)) return fail(ctx, ASL_EINVAL, "max_records out of range");
+  DeviceGuard guard(ctx->device);
+  if (guard.err != hipSuccess) return hip_fail(ctx, guard.err, "set device");
+  prof_release(ctx);
+  if (kernel_mask == 0 || max_records == 0) return ASL_OK;
+  asl::Prof& pf = ctx->prof;
+  pf.start = new (std::nothrow) hipEvent_t[max_records];
+  pf.stop = new (std::nothrow) hipEvent_t[max_records];
+  pf.id = new (std::nothrow) int[max_records];
+  if (!pf.start || !pf.stop || !pf.id) {
+    delete[] pf.start; delete[] pf.stop; delete[] pf.id;
+    pf = asl::Prof();
+    return fail(ctx, ASL_ENOMEM, "profile buffers");
+  }
+  for (int i = 0; i < max_records; ++i) {
+    hipError_t e = hipEventCreate(&pf.start[i]);
+    if (e == hipSuccess) e = hipEventCreate(&pf.stop[i]);
+    if (e != hipSuccess) {
+      pf.cap = i;
+      prof_release(ctx);
+      return hip_fail(ctx, e, "hipEventCreate");
+    }
+    pf.cap = i + 1;
+  }
+  pf.mask = kernel_mask;
+  pf.n = 0;
+  ctx->ws.prof = &ctx->prof;
+  return ASL_OK;
+}
+
+asl_status asl_profile_collect(asl_ctx* ctx, int32_t kernel_id, double* total_ms, int32_t* launches) {
+  if (!ctx) return ASL_EINVAL;
+  if (!total_ms || !launches) return fail(ctx, ASL_EINVAL, "null output pointer");
+  if (kernel_id < -1 || kernel_id >= asl::kKernCount) return fail(ctx, ASL_EINVAL, "unknown kernel id");
+  *total_ms = 0.0;
+  *launches = 0;
+  asl::Prof& pf = ctx->prof;
+  DeviceGuard guard(ctx->device);
+  if (guard.err != hipSuccess) return hip_fail(ctx, guard.err, "set device");
+  for (int i = 0; i < pf.n; ++i) {
+    if (pf.id[i] != kernel_id) continue;
+    hipError_t e = hipEventSynchronize(pf.stop[i]);
+    float ms = 0.f;
+    if (e == hipSuccess) e = hipEventElapsedTime(&ms, pf.start[i], pf.stop[i]);
+    if (e != hipSuccess) return hip_fail(ctx, e, "event read");
+    *total_ms += ms;
+    *launches += 1;
+  }
+  if (kernel_id == -1) pf.n = 0;          // -1: forget the records taken so far
+  return ASL_OK;
+}
+
 asl_status asl_destroy(asl_ctx* ctx) {
   if (!ctx) return ASL_EINVAL;
   DeviceGuard guard(ctx->device);
+  prof_release(ctx);
   hipError_t e = hipFree(ctx->base);
   delete ctx;
   return e == hipSuccess ? ASL_OK : ASL_EHIP;
@@ -193,7 +263,7 @@ asl_status asl_score_layer(asl_ctx* ctx, const asl_params* p, const void* q_obs,
   hipError_t e = asl::launch_score(*p, ctx->ws, q_obs, k, lse, hs);
   if (e != hipSuccess) return hip_fail(ctx, e, "score launch");
   const int T = p->seq_len - p->window;
-  e = asl::launch_pool(ctx->ws.u_group, p->n_kv_heads, T, p->pool_kernel, p_head, s_all, hs);
+  e = asl::launch_pool(ctx->ws.prof, ctx->ws.u_group, p->n_kv_heads, T, p->pool_kernel, p_head, s_all, hs);
   if (e != hipSuccess) return hip_fail(ctx, e, "pool launch");
   return ASL_OK;
 }
@@ -207,7 +277,7 @@ asl_status asl_pool(asl_ctx* ctx, const float* u, int32_t rows, int32_t T, int32
   if (S > kMaxPoolKernel) return fail(ctx, ASL_EUNSUPPORTED, "pool kernel S > %d not supported", kMaxPoolKernel);
   DeviceGuard guard(ctx->device);
   if (guard.err != hipSuccess) return hip_fail(ctx, guard.err, "set device");
-  hipError_t e = asl::launch_pool(u, rows, T, S, p_out, s_out, static_cast<hipStream_t>(stream));
+  hipError_t e = asl::launch_pool(ctx->ws.prof, u, rows, T, S, p_out, s_out, static_cast<hipStream_t>(stream));
   if (e != hipSuccess) return hip_fail(ctx, e, "pool launch");
   return ASL_OK;
 }
@@ -245,7 +315,7 @@ asl_status asl_rankvar(asl_ctx* ctx, const int32_t* rank_ring, int32_t l_obs, in
   if (guard.err != hipSuccess) return hip_fail(ctx, guard.err, "set device");
   hipStream_t hs = static_cast<hipStream_t>(stream);
   hipError_t e = (layer_idx < l_min)
-                     ? asl::launch_stat_skip(out, hs)
+                     ? asl::launch_stat_skip(ctx->ws.prof, out, hs)
                      : asl::launch_rankvar(ctx->ws, rank_ring, l_obs, T, layer_idx, k, tau, state, out, hs);
   if (e != hipSuccess) return hip_fail(ctx, e, "rankvar launch");
   return ASL_OK;
@@ -267,9 +337,9 @@ asl_status asl_rank_stat(asl_ctx* ctx, const asl_params* p, const float* s_all, 
   int32_t* row = rank_ring + (int64_t)(layer_idx % l_obs) * T;
   hipError_t e = asl::launch_rank(ctx->ws, s_all, T, row, hs);
   if (e != hipSuccess) return hip_fail(ctx, e, "rank launch");
-  e = asl::launch_ring_push(state, layer_idx, l_obs, hs);
+  e = asl::launch_ring_push(ctx->ws.prof, state, layer_idx, l_obs, hs);
   if (e != hipSuccess) return hip_fail(ctx, e, "ring push launch");
-  e = (layer_idx < l_min) ? asl::launch_stat_skip(out, hs)
+  e = (layer_idx < l_min) ? asl::launch_stat_skip(ctx->ws.prof, out, hs)
                           : asl::launch_rankvar(ctx->ws, rank_ring, l_obs, T, layer_idx, k, tau, state, out, hs);
   if (e != hipSuccess) return hip_fail(ctx, e, "rankvar launch");
   return ASL_OK;
@@ -314,7 +384,7 @@ asl_status asl_gather_kv(asl_ctx* ctx, const asl_params* p, const void* k, const
     return fail(ctx, ASL_EINVAL, "token stride smaller than head_dim");
   DeviceGuard guard(ctx->device);
   if (guard.err != hipSuccess) return hip_fail(ctx, guard.err, "set device");
-  hipError_t e = asl::launch_gather(k, v, idx, idx_rows, n_idx, p->n_kv_heads, (int)row_bytes,
+  hipError_t e = asl::launch_gather(ctx->ws.prof, k, v, idx, idx_rows, n_idx, p->n_kv_heads, (int)row_bytes,
                                     p->k_stride_head * eb, p->k_stride_tok * eb, p->v_stride_head * eb,
                                     p->v_stride_tok * eb, k_out, v_out, static_cast<hipStream_t>(stream));
   if (e != hipSuccess) return hip_fail(ctx, e, "gather launch");

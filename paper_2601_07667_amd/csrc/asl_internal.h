@@ -7,6 +7,45 @@
 
 namespace asl {
 
+// Kernel ids for the optional per-kernel event profiling (asl_profile_enable / asl_profile_collect).
+enum KernelId {
+  kKernRowstats = 0, kKernCombine, kKernColsum, kKernPool, kKernSortHist, kKernSortScatter,
+  kKernRingPush, kKernRankvar, kKernSelHist, kKernSelCount, kKernSelWrite, kKernGather,
+  kKernScoreGeneric, kKernCount
+};
+
+// Event pairs recorded around tagged launches; owned by the ctx, created by asl_profile_enable.
+struct Prof {
+  uint32_t mask = 0;
+  int cap = 0, n = 0;
+  hipEvent_t* start = nullptr;
+  hipEvent_t* stop = nullptr;
+  int* id = nullptr;
+};
+
+// Brackets one launch with a start/stop event pair when its kernel id is enabled.
+struct ProfScope {
+  Prof* p;
+  hipStream_t st;
+  int slot = -1;
+  ProfScope(Prof* prof, int kid, hipStream_t s) : p(prof), st(s) {
+    if (p && ((p->mask >> kid) & 1u) && p->n < p->cap) {
+      slot = p->n++;
+      p->id[slot] = kid;
+      (void)hipEventRecord(p->start[slot], st);
+    }
+  }
+  ~ProfScope() {
+    if (slot >= 0) (void)hipEventRecord(p->stop[slot], st);
+  }
+};
+
+#define ASL_LAUNCH(prof, kid, st, ...)        \
+  do {                                        \
+    asl::ProfScope ps_((prof), (kid), (st));  \
+    hipLaunchKernelGGL(__VA_ARGS__);          \
+  } while (0)
+
 // Workspace carve-up (device memory owned by the ctx).
 struct Workspace {
   // scoring
@@ -22,6 +61,7 @@ struct Workspace {
   uint32_t* sel_hist;      // [rows][256]
   uint32_t* sel_state;     // [rows][4]  {prefix, k_remaining, unused, unused}
   uint32_t* sel_tile_cnt;  // [rows][n_tiles][2]
+  Prof* prof;              // null unless profiling is enabled
 };
 
 constexpr int kSortTile = 2048;        // elements per radix-sort workgroup tile
@@ -38,16 +78,16 @@ constexpr int kCntSelTicket = 8;       // [max rows] tickets start here (up to 4
 
 hipError_t launch_score(const asl_params& p, const Workspace& ws, const void* q_obs, const void* k,
                         const float* lse, hipStream_t st);
-hipError_t launch_pool(const float* u, int rows, int T, int S, float* p_out, float* s_out,
+hipError_t launch_pool(Prof* prof, const float* u, int rows, int T, int S, float* p_out, float* s_out,
                        hipStream_t st);
 hipError_t launch_rank(const Workspace& ws, const float* s, int T, int32_t* rank_out, hipStream_t st);
-hipError_t launch_ring_push(asl_state* state, int layer_idx, int l_obs, hipStream_t st);
+hipError_t launch_ring_push(Prof* prof, asl_state* state, int layer_idx, int l_obs, hipStream_t st);
 hipError_t launch_rankvar(const Workspace& ws, const int32_t* ring, int l_obs, int T, int layer_idx,
                           int k, double tau, asl_state* state, asl_stat* out, hipStream_t st);
-hipError_t launch_stat_skip(asl_stat* out, hipStream_t st);
+hipError_t launch_stat_skip(Prof* prof, asl_stat* out, hipStream_t st);
 hipError_t launch_select(const Workspace& ws, const float* scores, int rows, int T, int k, int W,
                          int32_t* idx_out, hipStream_t st);
-hipError_t launch_gather(const void* k, const void* v, const int32_t* idx, int idx_rows, int n_idx,
+hipError_t launch_gather(Prof* prof, const void* k, const void* v, const int32_t* idx, int idx_rows, int n_idx,
                          int Hk, int row_bytes, int64_t k_stride_head_b, int64_t k_stride_tok_b,
                          int64_t v_stride_head_b, int64_t v_stride_tok_b, void* k_out, void* v_out,
                          hipStream_t st);

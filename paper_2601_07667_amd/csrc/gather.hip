@@ -27,7 +27,7 @@ gather_kernel(const char* __restrict__ k, const char* __restrict__ v, const int3
   }
 }
 
-hipError_t launch_gather(const void* k, const void* v, const int32_t* idx, int idx_rows, int n_idx,
+hipError_t launch_gather(Prof* prof, const void* k, const void* v, const int32_t* idx, int idx_rows, int n_idx,
                          int Hk, int row_bytes, int64_t ksh_b, int64_t kst_b, int64_t vsh_b,
                          int64_t vst_b, void* k_out, void* v_out, hipStream_t st) {
   const int cpr = row_bytes / 16;
@@ -36,7 +36,7 @@ hipError_t launch_gather(const void* k, const void* v, const int32_t* idx, int i
   if (total == 0) return hipSuccess;
   int64_t blocks = (total + 255) / 256;
   if (blocks > 65536) blocks = 65536;
-  hipLaunchKernelGGL(gather_kernel, dim3((unsigned)blocks), dim3(256), 0, st, (const char*)k,
+  ASL_LAUNCH(prof, kKernGather, st, gather_kernel, dim3((unsigned)blocks), dim3(256), 0, st, (const char*)k,
                      (const char*)v, idx, idx_rows, n_idx, Hk, cpr, ksh_b, kst_b, vsh_b, vst_b,
                      (char*)k_out, (char*)v_out, n_tensors);
   return hipGetLastError();

@@ -36,9 +36,9 @@ pool_kernel(const float* __restrict__ u, int rows, int T, int S, float* __restri
   if (s_out != nullptr && t < T) s_out[t] = total;
 }
 
-hipError_t launch_pool(const float* u, int rows, int T, int S, float* p_out, float* s_out,
+hipError_t launch_pool(Prof* prof, const float* u, int rows, int T, int S, float* p_out, float* s_out,
                        hipStream_t st) {
-  hipLaunchKernelGGL(pool_kernel, dim3((T + kPoolBlock - 1) / kPoolBlock), dim3(kPoolBlock), 0, st, u,
+  ASL_LAUNCH(prof, kKernPool, st, pool_kernel, dim3((T + kPoolBlock - 1) / kPoolBlock), dim3(kPoolBlock), 0, st, u,
                      rows, T, S, p_out, s_out);
   return hipGetLastError();
 }

@@ -141,20 +141,20 @@ hipError_t launch_rank(const Workspace& ws, const float* s, int T, int32_t* rank
   uint32_t* ticket = ws.counters + kCntSortTicket;
   const dim3 grid(n_tiles), block(kSortThreads);
   // pass 0: scores -> buffer 0
-  hipLaunchKernelGGL((sort_hist_kernel<true>), grid, block, 0, st, s, nullptr, T, 0, n_tiles, ws.tile_hist, ticket);
-  hipLaunchKernelGGL((sort_scatter_kernel<true, false>), grid, block, 0, st, s, nullptr, nullptr, T, 0,
+  ASL_LAUNCH(ws.prof, kKernSortHist, st, (sort_hist_kernel<true>), grid, block, 0, st, s, nullptr, T, 0, n_tiles, ws.tile_hist, ticket);
+  ASL_LAUNCH(ws.prof, kKernSortScatter, st, (sort_scatter_kernel<true, false>), grid, block, 0, st, s, nullptr, nullptr, T, 0,
                      n_tiles, ws.tile_hist, ws.sort_key[0], ws.sort_idx[0], nullptr);
   // pass 1: 0 -> 1
-  hipLaunchKernelGGL((sort_hist_kernel<false>), grid, block, 0, st, nullptr, ws.sort_key[0], T, 8, n_tiles, ws.tile_hist, ticket);
-  hipLaunchKernelGGL((sort_scatter_kernel<false, false>), grid, block, 0, st, nullptr, ws.sort_key[0],
+  ASL_LAUNCH(ws.prof, kKernSortHist, st, (sort_hist_kernel<false>), grid, block, 0, st, nullptr, ws.sort_key[0], T, 8, n_tiles, ws.tile_hist, ticket);
+  ASL_LAUNCH(ws.prof, kKernSortScatter, st, (sort_scatter_kernel<false, false>), grid, block, 0, st, nullptr, ws.sort_key[0],
                      ws.sort_idx[0], T, 8, n_tiles, ws.tile_hist, ws.sort_key[1], ws.sort_idx[1], nullptr);
   // pass 2: 1 -> 0
-  hipLaunchKernelGGL((sort_hist_kernel<false>), grid, block, 0, st, nullptr, ws.sort_key[1], T, 16, n_tiles, ws.tile_hist, ticket);
-  hipLaunchKernelGGL((sort_scatter_kernel<false, false>), grid, block, 0, st, nullptr, ws.sort_key[1],
+  ASL_LAUNCH(ws.prof, kKernSortHist, st, (sort_hist_kernel<false>), grid, block, 0, st, nullptr, ws.sort_key[1], T, 16, n_tiles, ws.tile_hist, ticket);
+  ASL_LAUNCH(ws.prof, kKernSortScatter, st, (sort_scatter_kernel<false, false>), grid, block, 0, st, nullptr, ws.sort_key[1],
                      ws.sort_idx[1], T, 16, n_tiles, ws.tile_hist, ws.sort_key[0], ws.sort_idx[0], nullptr);
   // pass 3: 0 -> rank
-  hipLaunchKernelGGL((sort_hist_kernel<false>), grid, block, 0, st, nullptr, ws.sort_key[0], T, 24, n_tiles, ws.tile_hist, ticket);
-  hipLaunchKernelGGL((sort_scatter_kernel<false, true>), grid, block, 0, st, nullptr, ws.sort_key[0],
+  ASL_LAUNCH(ws.prof, kKernSortHist, st, (sort_hist_kernel<false>), grid, block, 0, st, nullptr, ws.sort_key[0], T, 24, n_tiles, ws.tile_hist, ticket);
+  ASL_LAUNCH(ws.prof, kKernSortScatter, st, (sort_scatter_kernel<false, true>), grid, block, 0, st, nullptr, ws.sort_key[0],
                      ws.sort_idx[0], T, 24, n_tiles, ws.tile_hist, nullptr, nullptr, rank_out);
   return hipGetLastError();
 }

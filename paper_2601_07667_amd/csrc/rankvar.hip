@@ -124,13 +124,13 @@ rankvar_kernel(const int32_t* __restrict__ ring, int l_obs, int T, int layer_idx
   __hip_atomic_store(counters + kCntVarTicket, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-hipError_t launch_ring_push(asl_state* state, int layer_idx, int l_obs, hipStream_t st) {
-  hipLaunchKernelGGL(ring_push_kernel, dim3(1), dim3(64), 0, st, state, layer_idx, l_obs);
+hipError_t launch_ring_push(Prof* prof, asl_state* state, int layer_idx, int l_obs, hipStream_t st) {
+  ASL_LAUNCH(prof, kKernRingPush, st, ring_push_kernel, dim3(1), dim3(64), 0, st, state, layer_idx, l_obs);
   return hipGetLastError();
 }
 
-hipError_t launch_stat_skip(asl_stat* out, hipStream_t st) {
-  hipLaunchKernelGGL(stat_skip_kernel, dim3(1), dim3(64), 0, st, out);
+hipError_t launch_stat_skip(Prof* prof, asl_stat* out, hipStream_t st) {
+  ASL_LAUNCH(prof, kKernRingPush, st, stat_skip_kernel, dim3(1), dim3(64), 0, st, out);
   return hipGetLastError();
 }
 
@@ -138,7 +138,7 @@ hipError_t launch_rankvar(const Workspace& ws, const int32_t* ring, int l_obs, i
                           int k, double tau, asl_state* state, asl_stat* out, hipStream_t st) {
   int blocks = (T + kVarThreads - 1) / kVarThreads;
   if (blocks > 512) blocks = 512;
-  hipLaunchKernelGGL(rankvar_kernel, dim3(blocks), dim3(kVarThreads), 0, st, ring, l_obs, T, layer_idx, k,
+  ASL_LAUNCH(ws.prof, kKernRankvar, st, rankvar_kernel, dim3(blocks), dim3(kVarThreads), 0, st, ring, l_obs, T, layer_idx, k,
                      tau, state, out, ws.counters);
   return hipGetLastError();
 }

@@ -29,49 +29,44 @@ __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_ex
 // Row of the 32x32 accumulator held by register r of a lane in half `half` (lanes 32..63 = 1).
 __device__ __forceinline__ int acc_row(int r, int half) { return 8 * (r >> 2) + 4 * half + (r & 3); }
 
-template <int D, int NT>
-struct KTileLoader {
-  static constexpr int CPR = D / 8;                       // 16-byte chunks per key row
-  static constexpr int NLOAD = (KT * CPR + NT - 1) / NT;  // chunks per thread
-  static constexpr int ROW = D + 8;                       // padded LDS row, bf16 elements
+// Global -> register staging of one K tile (KT keys x D bf16), 16 bytes per thread per step;
+// rows past N are clamped to the last key (they are masked or discarded later).
+#define ASL_KTILE_DECL(D, NT)                                                                  \
+  constexpr int CPR = (D) / 8;                          /* 16-byte pieces per key row */       \
+  constexpr int NLOAD = (KT * CPR + (NT) - 1) / (NT);   /* pieces per thread */                \
   uint4 stage[NLOAD];
 
-  __device__ __forceinline__ void load(const __bf16* kg, int64_t kst, int key0, int N, int tid) {
-#pragma unroll
-    for (int i = 0; i < NLOAD; ++i) {
-      int q = tid + i * NT;
-      if (KT * CPR % NT == 0 || q < KT * CPR) {
-        int row = q / CPR, col = q % CPR;
-        int key = min(key0 + row, N - 1);                 // clamp: rows past N are masked later
-        stage[i] = *reinterpret_cast<const uint4*>(kg + (int64_t)key * kst + col * 8);
-      }
-    }
+#define ASL_KTILE_LOAD(key0)                                                                    \
+  _Pragma("unroll") for (int i_ = 0; i_ < NLOAD; ++i_) {                                        \
+    const int q_ = tid + i_ * NT;                                                               \
+    const int row_ = q_ / CPR, col_ = q_ % CPR;                                                 \
+    const int key_ = min((key0) + row_, N - 1);                                                 \
+    uint4 v_ = make_uint4(0u, 0u, 0u, 0u);                                                      \
+    if (q_ < KT * CPR) v_ = *reinterpret_cast<const uint4*>(kg + (int64_t)key_ * kst + col_ * 8); \
+    stage[i_] = v_;                                                                             \
   }
-  __device__ __forceinline__ void store(__bf16* lds, int tid) {
-#pragma unroll
-    for (int i = 0; i < NLOAD; ++i) {
-      int q = tid + i * NT;
-      if (KT * CPR % NT == 0 || q < KT * CPR) {
-        int row = q / CPR, col = q % CPR;
-        *reinterpret_cast<uint4*>(lds + row * ROW + col * 8) = stage[i];
-      }
-    }
-  }
-};
 
-template <int D>
-__device__ __forceinline__ void load_q_frags(const __bf16* qg, int qrow, int M, int half,
-                                             bf16x8 (&qf)[D / 16]) {
-#pragma unroll
-  for (int ks = 0; ks < D / 16; ++ks) {
-    if (qrow < M) {
-      qf[ks] = *reinterpret_cast<const bf16x8*>(qg + (int64_t)qrow * D + ks * 16 + half * 8);
-    } else {
-      bf16x8 z = {0, 0, 0, 0, 0, 0, 0, 0};
-      qf[ks] = z;
-    }
+#define ASL_KTILE_STORE()                                                                       \
+  _Pragma("unroll") for (int i_ = 0; i_ < NLOAD; ++i_) {                                        \
+    const int q_ = tid + i_ * NT;                                                               \
+    const int row_ = q_ / CPR, col_ = q_ % CPR;                                                 \
+    if (q_ < KT * CPR) *reinterpret_cast<uint4*>(lds_k + row_ * ROW + col_ * 8) = stage[i_];    \
   }
-}
+
+// Query fragments of this wave's 32-row block: lane (ln, half) holds row ln, d = 16*ks + 8*half .. +8.
+#define ASL_LOAD_Q_FRAGS()                                                                      \
+  bf16x8 qf[KS];                                                                                \
+  {                                                                                             \
+    const __bf16* qg_ = q_obs + (int64_t)g * M * D + (int64_t)min(qrow, M - 1) * D + half * 8;  \
+    _Pragma("unroll") for (int ks = 0; ks < KS; ++ks) {                                         \
+      uint4 raw_ = *reinterpret_cast<const uint4*>(qg_ + ks * 16);                              \
+      if (qrow >= M) raw_ = make_uint4(0u, 0u, 0u, 0u);     /* padded rows: zero queries */     \
+      qf[ks] = __builtin_bit_cast(bf16x8, raw_);                                                \
+    }                                                                                           \
+  }
+
+// max without NaN canonicalisation (inputs are never NaN here; -inf is fine)
+__device__ __forceinline__ float max2(float a, float b) { return a > b ? a : b; }
 
 // ---------------------------------------------------------------------------------------------
 // Pass 1: per-row running (max, sum) over this workgroup's key chunk, in the log2 domain.
@@ -91,9 +86,7 @@ score_rowstats_kernel(const __bf16* __restrict__ q_obs, const __bf16* __restrict
   const int T = N - W;
   const int qrow = wave * 32 + ln;
   const int wi = qrow % W;                      // window row of this lane's query row
-
-  bf16x8 qf[KS];
-  load_q_frags<D>(q_obs + (int64_t)g * M * D, qrow, M, half, qf);
+  ASL_LOAD_Q_FRAGS();
 
   const __bf16* kg = k + (int64_t)g * ksh;
   const int n_tiles_total = (N + KT - 1) / KT;
@@ -101,14 +94,14 @@ score_rowstats_kernel(const __bf16* __restrict__ q_obs, const __bf16* __restrict
   const int tile_end = min(tile0 + tiles_per_chunk, n_tiles_total);
 
   float m_run = kNegBig, z_run = 0.f;
-  KTileLoader<D, NT> ld;
-  if (tile0 < tile_end) ld.load(kg, kst, tile0 * KT, N, tid);
+  ASL_KTILE_DECL(D, NT);
+  if (tile0 < tile_end) { ASL_KTILE_LOAD(tile0 * KT); }
 
   for (int tile = tile0; tile < tile_end; ++tile) {
     __syncthreads();                            // every wave is done reading the previous tile
-    ld.store(lds_k, tid);
+    ASL_KTILE_STORE();
     __syncthreads();
-    if (tile + 1 < tile_end) ld.load(kg, kst, (tile + 1) * KT, N, tid);
+    if (tile + 1 < tile_end) { ASL_KTILE_LOAD((tile + 1) * KT); }
 
     const int kbase = tile * KT;
     const bool need_mask = (kbase + KT > T);    // touches the window block or the tail past N
@@ -123,30 +116,31 @@ score_rowstats_kernel(const __bf16* __restrict__ q_obs, const __bf16* __restrict
         bf16x8 kf = *reinterpret_cast<const bf16x8*>(krow + ks * 16);
         acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], acc, 0, 0, 0);   // [key][query row]
       }
+      float x[16];
+#pragma unroll
+      for (int r = 0; r < 16; ++r) x[r] = acc[r];
       if (need_mask) {
+        // visible iff key < N and (key < T or key - T <= wi)  <=>  key < min(N, T + wi + 1)
+        const int lim = min(N, T + wi + 1) - (kbase + sub * 32 + 4 * half);
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          int key = kbase + sub * 32 + acc_row(r, half);
-          bool masked = (key >= N) || (key >= T && (key - T) > wi);
-          if (masked) acc[r] = -INFINITY;
-        }
+        for (int r = 0; r < 16; ++r) x[r] = (8 * (r >> 2) + (r & 3) < lim) ? x[r] : -INFINITY;
       }
-      float mx = acc[0];
+      float mx = x[0];
 #pragma unroll
-      for (int r = 1; r < 16; r += 2) mx = fmaxf(mx, fmaxf(acc[r], acc[(r + 1) & 15]));
-      const float m_new = fmaxf(m_run, mx * c1);
+      for (int r = 1; r < 16; ++r) mx = max2(mx, x[r]);
+      const float m_new = max2(m_run, mx * c1);
       float sum = 0.f;
 #pragma unroll
-      for (int r = 0; r < 16; ++r) sum += fast_exp2(fmaf(acc[r], c1, -m_new));
+      for (int r = 0; r < 16; ++r) sum += fast_exp2(fmaf(x[r], c1, -m_new));
       z_run = z_run * fast_exp2(m_run - m_new) + sum;
       m_run = m_new;
     }
   }
   // the two lane halves hold disjoint keys of the same query row
   const float m_o = __shfl_xor(m_run, 32), z_o = __shfl_xor(z_run, 32);
-  const float m = fmaxf(m_run, m_o);
-  const float z = (half == 0) ? (z_run * fast_exp2(m_run - m) + z_o * fast_exp2(m_o - m))
-                              : (z_o * fast_exp2(m_o - m) + z_run * fast_exp2(m_run - m));
+  const float m = max2(m_run, m_o);
+  const float za = z_run * fast_exp2(m_run - m), zb = z_o * fast_exp2(m_o - m);
+  const float z = (half == 0) ? (za + zb) : (zb + za);
   if (half == 0 && qrow < M) {
     float* dst = row_part + ((int64_t)(g * n_chunks + chunk) * M + qrow) * 2;
     dst[0] = m;
@@ -185,15 +179,14 @@ score_colsum_kernel(const __bf16* __restrict__ q_obs, const __bf16* __restrict__
   const int g = blockIdx.x % Hk, chunk = blockIdx.x / Hk;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, ln = lane & 31, half = lane >> 5;
   const int qrow = wave * 32 + ln;
-
-  bf16x8 qf[KS];
-  load_q_frags<D>(q_obs + (int64_t)g * M * D, qrow, M, half, qf);
+  ASL_LOAD_Q_FRAGS();
 
   float rc[16];
 #pragma unroll
   for (int r = 0; r < 16; ++r) {
-    int row = wave * 32 + acc_row(r, half);
-    rc[r] = (row < M) ? row_const[(int64_t)g * M + row] * rc_mul : INFINITY;   // padded rows add 0
+    const int row = wave * 32 + acc_row(r, half);
+    const float v = row_const[(int64_t)g * M + min(row, M - 1)] * rc_mul;
+    rc[r] = (row < M) ? v : INFINITY;                    // padded rows add 2^-inf = 0
   }
 
   const __bf16* kg = k + (int64_t)g * ksh;
@@ -201,14 +194,14 @@ score_colsum_kernel(const __bf16* __restrict__ q_obs, const __bf16* __restrict__
   const int tile0 = chunk * tiles_per_chunk;
   const int tile_end = min(tile0 + tiles_per_chunk, n_tiles_total);
 
-  KTileLoader<D, NT> ld;
-  if (tile0 < tile_end) ld.load(kg, kst, tile0 * KT, N, tid);
+  ASL_KTILE_DECL(D, NT);
+  if (tile0 < tile_end) { ASL_KTILE_LOAD(tile0 * KT); }
 
   for (int tile = tile0; tile < tile_end; ++tile) {
     __syncthreads();                            // previous tile's LDS reads (keys and red) are done
-    ld.store(lds_k, tid);
+    ASL_KTILE_STORE();
     __syncthreads();
-    if (tile + 1 < tile_end) ld.load(kg, kst, (tile + 1) * KT, N, tid);
+    if (tile + 1 < tile_end) { ASL_KTILE_LOAD((tile + 1) * KT); }
 
     const int kbase = tile * KT;
 #pragma unroll
@@ -330,17 +323,17 @@ static hipError_t launch_score_mfma(const asl_params& p, const Workspace& ws, co
   const int n_tiles1 = (N + KT - 1) / KT;
   const int tpc1 = (n_tiles1 + n_chunks - 1) / n_chunks;
   if (!lse) {
-    hipLaunchKernelGGL((score_rowstats_kernel<D, NW>), dim3(Hk * n_chunks), dim3(NW * 64), 0, st, q, k,
+    ASL_LAUNCH(ws.prof, kKernRowstats, st, (score_rowstats_kernel<D, NW>), dim3(Hk * n_chunks), dim3(NW * 64), 0, st, q, k,
                        p.k_stride_head, p.k_stride_tok, Hk, M, p.window, N, tpc1, n_chunks, c1,
                        ws.row_part);
     const int rows = Hk * M;
-    hipLaunchKernelGGL(score_combine_kernel, dim3((rows + 255) / 256), dim3(256), 0, st, ws.row_part,
+    ASL_LAUNCH(ws.prof, kKernCombine, st, score_combine_kernel, dim3((rows + 255) / 256), dim3(256), 0, st, ws.row_part,
                        Hk, M, n_chunks, ws.row_const);
   }
   const int n_tiles2 = (T + KT - 1) / KT;
   const int tpc2 = (n_tiles2 + n_chunks - 1) / n_chunks;
   const int n_chunks2 = (n_tiles2 + tpc2 - 1) / tpc2;
-  hipLaunchKernelGGL((score_colsum_kernel<D, NW>), dim3(Hk * n_chunks2), dim3(NW * 64), 0, st, q, k,
+  ASL_LAUNCH(ws.prof, kKernColsum, st, (score_colsum_kernel<D, NW>), dim3(Hk * n_chunks2), dim3(NW * 64), 0, st, q, k,
                      p.k_stride_head, p.k_stride_tok, Hk, M, N, T, tpc2, c1,
                      lse ? lse : ws.row_const, lse ? kLog2e : 1.0f, ws.u_group);
   return hipGetLastError();
@@ -368,10 +361,10 @@ static hipError_t launch_score_generic(const asl_params& p, const Workspace& ws,
   const int D = p.head_dim;
   if (!lse) {
     size_t sm = (size_t)(D + 512) * sizeof(float);
-    hipLaunchKernelGGL((score_rowstats_generic<TIn>), dim3(p.n_q_heads * W), dim3(256), sm, st, q, k,
+    ASL_LAUNCH(ws.prof, kKernScoreGeneric, st, (score_rowstats_generic<TIn>), dim3(p.n_q_heads * W), dim3(256), sm, st, q, k,
                        p.k_stride_head, p.k_stride_tok, G, W, N, D, c1, ws.row_const);
   }
-  hipLaunchKernelGGL((score_colsum_generic<TIn>), dim3((T + 255) / 256, Hk), dim3(256), 0, st, q, k,
+  ASL_LAUNCH(ws.prof, kKernScoreGeneric, st, (score_colsum_generic<TIn>), dim3((T + 255) / 256, Hk), dim3(256), 0, st, q, k,
                      p.k_stride_head, p.k_stride_tok, M, T, D, c1, lse ? lse : ws.row_const,
                      lse ? kLog2e : 1.0f, ws.u_group);
   return hipGetLastError();

@@ -192,11 +192,11 @@ hipError_t launch_select(const Workspace& ws, const float* scores, int rows, int
   const dim3 grid(n_tiles, rows), block(kSelThreads);
   uint32_t* tickets = ws.counters + kCntSelTicket;
   for (int pass = 0; pass < 4; ++pass)
-    hipLaunchKernelGGL(select_hist_kernel, grid, block, 0, st, scores, T, pass, k, ws.sel_hist,
+    ASL_LAUNCH(ws.prof, kKernSelHist, st, select_hist_kernel, grid, block, 0, st, scores, T, pass, k, ws.sel_hist,
                        ws.sel_state, tickets);
-  hipLaunchKernelGGL(select_count_kernel, grid, block, 0, st, scores, T, n_tiles, ws.sel_state,
+  ASL_LAUNCH(ws.prof, kKernSelCount, st, select_count_kernel, grid, block, 0, st, scores, T, n_tiles, ws.sel_state,
                      ws.sel_tile_cnt);
-  hipLaunchKernelGGL(select_write_kernel, grid, block, 0, st, scores, T, n_tiles, k, W, ws.sel_state,
+  ASL_LAUNCH(ws.prof, kKernSelWrite, st, select_write_kernel, grid, block, 0, st, scores, T, n_tiles, k, W, ws.sel_state,
                      ws.sel_tile_cnt, idx_out);
   return hipGetLastError();
 }
