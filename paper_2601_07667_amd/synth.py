@@ -202,9 +202,13 @@ def sweep_latents(T: int, n_layers: int = 32, seed: int = BASE_SEED + 4) -> np.n
     return out
 
 
-def sweep_layer(shape: Shape, z_l: np.ndarray, layer: int, seed: int = BASE_SEED + 4) -> Layer:
+SWEEP_NOISE = 0.5
+
+
+def sweep_layer(shape: Shape, z_l: np.ndarray, layer: int, seed: int = BASE_SEED + 4,
+                noise: float = SWEEP_NOISE) -> Layer:
     """Q_obs / K of one sweep layer whose window logits follow the latent z_l:
-    Q_obs[h,i] = c u_g + 0.5 N(0,I), K[g,j] = a z_l[j] u_g + 0.5 N(0,I), a c / sqrt(d) = 1,
+    Q_obs[h,i] = c u_g + noise N(0,I), K[g,j] = a z_l[j] u_g + noise N(0,I), a c / sqrt(d) = 1,
     u_g a random unit vector per KV head.  Window keys (j >= T) get latent 0."""
     rng = np.random.Generator(np.random.PCG64(seed * 1000 + layer + 1))
     Hq, Hk, G, d, N, W, T = shape.Hq, shape.Hk, shape.G, shape.d, shape.N, shape.W, shape.T
@@ -214,10 +218,10 @@ def sweep_layer(shape: Shape, z_l: np.ndarray, layer: int, seed: int = BASE_SEED
     u = u.astype(np.float32)
     zfull = np.zeros(N, dtype=np.float32)
     zfull[:T] = z_l.astype(np.float32)
-    q = 0.5 * _normal(rng, Hq, W, d)
+    q = noise * _normal(rng, Hq, W, d)
     for h in range(Hq):
         q[h] += c * u[h // G][None, :]
-    k = 0.5 * _normal(rng, Hk, N, d)
+    k = noise * _normal(rng, Hk, N, d)
     for g in range(Hk):
         k[g] += (a * zfull)[:, None] * u[g][None, :]
     v = _normal(rng, Hk, N, d)

@@ -128,29 +128,35 @@ def test_config3_literal_needles_are_not_recoverable(gpu_device):
 
 
 def test_config4_sweep_selection_layer(gpu_device):
-    """32-layer sweep: the GPU must pick the same selection layer as the oracle (tau margin
-    asserted in the oracle so the agreement is meaningful)."""
+    """32-layer sweep through the whole pipeline: the GPU must pick the same selection layer as the
+    oracle.  With this recipe the relative variance falls to about 0.34 at the last layer, so the
+    run uses tau = 0.5 from the paper's ablation grid (selection near layer 29); the first-crossing
+    layer is also compared for the other grid values whose oracle margin is large enough to make
+    the agreement meaningful."""
     import torch
     sh = synth.shape_of(4)
+    tau = 0.5
     z = synth.sweep_latents(sh.T, sh.n_layers)
     ctx = gu.ctx_for(sh)
     ring = torch.zeros((sh.L_obs, sh.T), dtype=torch.int32, device=gpu_device)
     state = asl.new_state(gpu_device)
     ost = orc.SelectState.new(sh.L_obs)
     sel_gpu = sel_ref = None
+    rel_ref, rel_gpu = {}, {}
     for l in range(sh.n_layers):
         L = synth.sweep_layer(sh, z[l], l)
-        out = _pipeline(gpu_device, L, layer_idx=l, ctx=ctx, state=state, ring=ring)
+        out = _pipeline(gpu_device, L, layer_idx=l, ctx=ctx, state=state, ring=ring, tau=tau)
         _, s_ref = orc.score_layer(L.q_obs, L.k, sh.W, sh.S)
         gu.assert_scores_close(out["s"], s_ref, f"sweep layer {l} s")
         ost.push(l, orc.rank_desc(s_ref))
-        d = orc.select_tokens(ost, l, sh.budget, sh.W, sh.L_min, sh.tau)
+        d = orc.select_tokens(ost, l, sh.budget, sh.W, sh.L_min, tau)
         st = out["stat"]
         print(f"layer {l}: oracle rel={d.rel_var:.4f} gpu rel={st.rel_var:.4f} union {d.union_size}/{st.union_size}",
               flush=True)
         assert bool(st.evaluated) == d.evaluated
         if d.evaluated:
-            assert abs(d.rel_var - sh.tau) > 1e-3, "oracle decision too close to tau: reseed"
+            rel_ref[l], rel_gpu[l] = d.rel_var, st.rel_var
+            assert abs(d.rel_var - tau) > 1e-3, "oracle decision too close to tau: reseed"
             assert abs(st.rel_var - d.rel_var) < 2e-2 * max(d.rel_var, 1e-3)
             assert bool(st.selected) == d.selected
         if d.selected:
@@ -159,6 +165,11 @@ def test_config4_sweep_selection_layer(gpu_device):
             break
     assert sel_ref is not None and sh.L_min < sel_ref <= 31 and sel_gpu == sel_ref
     assert asl.read_struct(state, asl.AslState).n_valid_rows == 0      # rank cache released
+    assert rel_ref[sh.L_min] == 1.0 and rel_gpu[sh.L_min] == 1.0       # relative variance is 1 at L_min
+    first = lambda rel, t: next((l for l in sorted(rel) if rel[l] < t), None)
+    for t in (0.6, 0.7, 0.8, 0.9):
+        if min(abs(r - t) for r in rel_ref.values()) > 1e-3:
+            assert first(rel_ref, t) == first(rel_gpu, t)
     ctx.close()
 
 
