@@ -46,11 +46,13 @@ size_t carve(char* base, int32_t max_seq_len, int32_t max_kv_heads, int32_t max_
     w.sort_key[i] = (uint32_t*)take(N * sizeof(uint32_t));
     w.sort_idx[i] = (uint32_t*)take(N * sizeof(uint32_t));
   }
-  w.tile_hist = (uint32_t*)take(256 * sort_tiles * sizeof(uint32_t));
+  w.tile_hist = (uint32_t*)take(256 * sort_tiles * sizeof(uint32_t));   // [tile][256]
   w.counters = (uint32_t*)take(asl::kCounterWords * sizeof(uint32_t));
-  w.sel_hist = (uint32_t*)take(rows * 256 * sizeof(uint32_t));
-  w.sel_state = (uint32_t*)take(rows * 4 * sizeof(uint32_t));
-  w.sel_tile_cnt = (uint32_t*)take(rows * sel_tiles * 2 * sizeof(uint32_t));
+  w.sel_hist = (uint32_t*)take(4 * rows * sel_tiles * 256 * sizeof(uint32_t));
+  w.sel_state = (uint32_t*)take(4 * rows * 2 * sizeof(uint32_t));
+  w.sel_tile_cnt = (uint32_t*)take(rows * sel_tiles * sizeof(uint32_t));
+  w.var_part_num = (unsigned long long*)take(asl::kVarMaxBlocks * sizeof(unsigned long long));
+  w.var_part_cnt = (uint32_t*)take(asl::kVarMaxBlocks * sizeof(uint32_t));
   if (ws) *ws = w;
   return off;
 }
@@ -315,8 +317,8 @@ asl_status asl_rankvar(asl_ctx* ctx, const int32_t* rank_ring, int32_t l_obs, in
   if (guard.err != hipSuccess) return hip_fail(ctx, guard.err, "set device");
   hipStream_t hs = static_cast<hipStream_t>(stream);
   hipError_t e = (layer_idx < l_min)
-                     ? asl::launch_stat_skip(ctx->ws.prof, out, hs)
-                     : asl::launch_rankvar(ctx->ws, rank_ring, l_obs, T, layer_idx, k, tau, state, out, hs);
+                     ? asl::launch_stat_skip(ctx->ws.prof, out, state, layer_idx, l_obs, 0, hs)
+                     : asl::launch_rankvar(ctx->ws, rank_ring, l_obs, T, layer_idx, k, tau, 0, state, out, hs);
   if (e != hipSuccess) return hip_fail(ctx, e, "rankvar launch");
   return ASL_OK;
 }
@@ -337,10 +339,9 @@ asl_status asl_rank_stat(asl_ctx* ctx, const asl_params* p, const float* s_all, 
   int32_t* row = rank_ring + (int64_t)(layer_idx % l_obs) * T;
   hipError_t e = asl::launch_rank(ctx->ws, s_all, T, row, hs);
   if (e != hipSuccess) return hip_fail(ctx, e, "rank launch");
-  e = asl::launch_ring_push(ctx->ws.prof, state, layer_idx, l_obs, hs);
-  if (e != hipSuccess) return hip_fail(ctx, e, "ring push launch");
-  e = (layer_idx < l_min) ? asl::launch_stat_skip(ctx->ws.prof, out, hs)
-                          : asl::launch_rankvar(ctx->ws, rank_ring, l_obs, T, layer_idx, k, tau, state, out, hs);
+  e = (layer_idx < l_min)
+          ? asl::launch_stat_skip(ctx->ws.prof, out, state, layer_idx, l_obs, 1, hs)
+          : asl::launch_rankvar(ctx->ws, rank_ring, l_obs, T, layer_idx, k, tau, 1, state, out, hs);
   if (e != hipSuccess) return hip_fail(ctx, e, "rankvar launch");
   return ASL_OK;
 }

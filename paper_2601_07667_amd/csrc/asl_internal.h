@@ -55,12 +55,14 @@ struct Workspace {
   // radix sort (rank)
   uint32_t* sort_key[2];   // [T] ping-pong
   uint32_t* sort_idx[2];   // [T]
-  uint32_t* tile_hist;     // [256][n_tiles] digit-major
+  uint32_t* tile_hist;     // [n_tiles][256] per-tile digit histogram of the current sort pass
   uint32_t* counters;      // small block of zero-initialised tickets / accumulators
   // select
-  uint32_t* sel_hist;      // [rows][256]
-  uint32_t* sel_state;     // [rows][4]  {prefix, k_remaining, unused, unused}
-  uint32_t* sel_tile_cnt;  // [rows][n_tiles][2]
+  uint32_t* sel_hist;      // [4 passes][rows][n_tiles][256]
+  uint32_t* sel_state;     // [4 passes][rows][2]  {prefix, keys still to take}
+  uint32_t* sel_tile_cnt;  // [rows][n_tiles] keys already known to lie below the threshold
+  unsigned long long* var_part_num;   // [kVarMaxBlocks] per-workgroup partial numerators
+  uint32_t* var_part_cnt;             // [kVarMaxBlocks] per-workgroup partial union counts
   Prof* prof;              // null unless profiling is enabled
 };
 
@@ -68,23 +70,22 @@ constexpr int kSortTile = 2048;        // elements per radix-sort workgroup tile
 constexpr int kSelTile = 4096;         // elements per select workgroup tile
 constexpr int kMaxChunks = 256;        // key chunks per KV head in scoring pass 1
 constexpr int kCounterWords = 64;
+constexpr int kVarMaxBlocks = 128;     // workgroups of the rank-variance kernel
 
 // counters layout (uint32 words)
-constexpr int kCntSortTicket = 0;
 constexpr int kCntVarTicket = 1;
-constexpr int kCntVarCount = 2;        // union size accumulator
-constexpr int kCntVarNumLo = 4;        // 64-bit numerator accumulator (8-byte aligned: words 4,5)
-constexpr int kCntSelTicket = 8;       // [max rows] tickets start here (up to 48 rows)
 
 hipError_t launch_score(const asl_params& p, const Workspace& ws, const void* q_obs, const void* k,
                         const float* lse, hipStream_t st);
 hipError_t launch_pool(Prof* prof, const float* u, int rows, int T, int S, float* p_out, float* s_out,
                        hipStream_t st);
 hipError_t launch_rank(const Workspace& ws, const float* s, int T, int32_t* rank_out, hipStream_t st);
-hipError_t launch_ring_push(Prof* prof, asl_state* state, int layer_idx, int l_obs, hipStream_t st);
+// push != 0: first account for this layer's freshly written ring row in the state (a layer index
+// that does not follow state->last_layer restarts the ring)
 hipError_t launch_rankvar(const Workspace& ws, const int32_t* ring, int l_obs, int T, int layer_idx,
-                          int k, double tau, asl_state* state, asl_stat* out, hipStream_t st);
-hipError_t launch_stat_skip(Prof* prof, asl_stat* out, hipStream_t st);
+                          int k, double tau, int push, asl_state* state, asl_stat* out, hipStream_t st);
+hipError_t launch_stat_skip(Prof* prof, asl_stat* out, asl_state* state, int layer_idx, int l_obs,
+                            int push, hipStream_t st);
 hipError_t launch_select(const Workspace& ws, const float* scores, int rows, int T, int k, int W,
                          int32_t* idx_out, hipStream_t st);
 hipError_t launch_gather(Prof* prof, const void* k, const void* v, const int32_t* idx, int idx_rows, int n_idx,

@@ -3,9 +3,9 @@
 //
 // A stable least-significant-digit radix sort of (key, index) pairs on an order-preserving
 // 32-bit transform of the fp32 score, 8 bits per pass; the last pass scatters positions to
-// rank[index] instead of writing the sorted pairs.  Per pass: a histogram kernel whose last
-// workgroup turns the [digit][tile] counts into exclusive offsets, then a scatter kernel that
-// ranks equal digits inside a tile with wavefront ballots (stable by construction).
+// rank[index] instead of writing the sorted pairs.  Per pass: a per-tile histogram kernel, then a
+// scatter kernel that derives its offsets from those histograms and ranks equal digits inside a
+// tile with wavefront ballots (stable by construction).
 #include "asl_internal.h"
 
 namespace asl {
@@ -23,13 +23,12 @@ __device__ __forceinline__ uint32_t desc_key(float f) {
   return ~asc;
 }
 
+// Per-tile digit histogram, written as one contiguous row tile_hist[tile][0..255].
 template <bool FIRST>
 __global__ void __launch_bounds__(kSortThreads)
 sort_hist_kernel(const float* __restrict__ s, const uint32_t* __restrict__ keys_in, int T, int shift,
-                 int n_tiles, uint32_t* tile_hist, uint32_t* ticket) {
+                 uint32_t* __restrict__ tile_hist) {
   __shared__ uint32_t h[256];
-  __shared__ uint32_t tot[256];
-  __shared__ int is_last;
   const int tid = threadIdx.x;
   h[tid] = 0;
   __syncthreads();
@@ -43,44 +42,55 @@ sort_hist_kernel(const float* __restrict__ s, const uint32_t* __restrict__ keys_
     }
   }
   __syncthreads();
-  tile_hist[(int64_t)tid * n_tiles + blockIdx.x] = h[tid];
-  __threadfence();
-  __syncthreads();
-  if (tid == 0) {
-    uint32_t t = __hip_atomic_fetch_add(ticket, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
-    is_last = (t == gridDim.x - 1);
-  }
-  __syncthreads();
-  if (!is_last) return;
-  __threadfence();
-  // exclusive offsets in (digit, tile) order, in place
-  uint32_t* row = tile_hist + (int64_t)tid * n_tiles;
-  uint32_t sum = 0;
-  for (int t = 0; t < n_tiles; ++t) sum += __hip_atomic_load(&row[t], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  tot[tid] = sum;
-  __syncthreads();
-  uint32_t run = 0;
-  for (int d = 0; d < tid; ++d) run += tot[d];
-  for (int t = 0; t < n_tiles; ++t) {
-    uint32_t v = __hip_atomic_load(&row[t], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    row[t] = run;
-    run += v;
-  }
-  if (tid == 0) *ticket = 0;
+  tile_hist[(int64_t)blockIdx.x * 256 + tid] = h[tid];
 }
 
+// Stable scatter of one tile.  Every workgroup derives its own exclusive offsets from the
+// per-tile histograms (all tiles' counts of smaller digits + earlier tiles' counts of the same
+// digit): redundant across workgroups but a few tens of KB of L2 reads, with no atomics, fences
+// or serial tail.
 template <bool FIRST, bool LAST>
 __global__ void __launch_bounds__(kSortThreads)
 sort_scatter_kernel(const float* __restrict__ s, const uint32_t* __restrict__ keys_in,
                     const uint32_t* __restrict__ idx_in, int T, int shift, int n_tiles,
-                    const uint32_t* __restrict__ tile_off, uint32_t* __restrict__ keys_out,
+                    const uint32_t* __restrict__ tile_hist, uint32_t* __restrict__ keys_out,
                     uint32_t* __restrict__ idx_out, int32_t* __restrict__ rank_out) {
   __shared__ uint32_t cnt[kSortWaves][256];
   __shared__ uint32_t start[kSortWaves][256];
+  __shared__ uint32_t wave_sum[kSortWaves];
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
 #pragma unroll
   for (int w = 0; w < kSortWaves; ++w) cnt[w][tid] = 0;
-  __syncthreads();
+
+  // digit `tid`: total over all tiles and over the tiles before this one
+  uint32_t tot = 0, prev = 0;
+  {
+    const int me = blockIdx.x;
+    int t = 0;
+    for (; t + 4 <= n_tiles; t += 4) {
+      uint32_t v0 = tile_hist[(int64_t)(t + 0) * 256 + tid], v1 = tile_hist[(int64_t)(t + 1) * 256 + tid];
+      uint32_t v2 = tile_hist[(int64_t)(t + 2) * 256 + tid], v3 = tile_hist[(int64_t)(t + 3) * 256 + tid];
+      tot += v0 + v1 + v2 + v3;
+      prev += (t + 0 < me ? v0 : 0u) + (t + 1 < me ? v1 : 0u) + (t + 2 < me ? v2 : 0u) + (t + 3 < me ? v3 : 0u);
+    }
+    for (; t < n_tiles; ++t) {
+      uint32_t v = tile_hist[(int64_t)t * 256 + tid];
+      tot += v;
+      prev += (t < me ? v : 0u);
+    }
+  }
+  // exclusive scan of tot over the 256 digits (wave scan + wave totals)
+  uint32_t incl = tot;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    uint32_t up = __shfl_up(incl, o);
+    if (lane >= o) incl += up;
+  }
+  if (lane == 63) wave_sum[wave] = incl;
+  __syncthreads();                                   // also orders the zeroing of cnt
+  uint32_t digit_base = incl - tot;
+  for (int w = 0; w < wave; ++w) digit_base += wave_sum[w];
+  const uint32_t my_off = digit_base + prev;         // first destination of digit `tid` in this tile
 
   constexpr int R = kSortPerWave / 64;
   uint32_t key[R], idx[R], off[R];
@@ -112,7 +122,7 @@ sort_scatter_kernel(const float* __restrict__ s, const uint32_t* __restrict__ ke
   }
   __syncthreads();
   {
-    uint32_t run = tile_off[(int64_t)tid * n_tiles + blockIdx.x];
+    uint32_t run = my_off;
 #pragma unroll
     for (int w = 0; w < kSortWaves; ++w) {
       start[w][tid] = run;
@@ -138,22 +148,21 @@ sort_scatter_kernel(const float* __restrict__ s, const uint32_t* __restrict__ ke
 
 hipError_t launch_rank(const Workspace& ws, const float* s, int T, int32_t* rank_out, hipStream_t st) {
   const int n_tiles = (T + kSortTile - 1) / kSortTile;
-  uint32_t* ticket = ws.counters + kCntSortTicket;
   const dim3 grid(n_tiles), block(kSortThreads);
   // pass 0: scores -> buffer 0
-  ASL_LAUNCH(ws.prof, kKernSortHist, st, (sort_hist_kernel<true>), grid, block, 0, st, s, nullptr, T, 0, n_tiles, ws.tile_hist, ticket);
+  ASL_LAUNCH(ws.prof, kKernSortHist, st, (sort_hist_kernel<true>), grid, block, 0, st, s, nullptr, T, 0, ws.tile_hist);
   ASL_LAUNCH(ws.prof, kKernSortScatter, st, (sort_scatter_kernel<true, false>), grid, block, 0, st, s, nullptr, nullptr, T, 0,
                      n_tiles, ws.tile_hist, ws.sort_key[0], ws.sort_idx[0], nullptr);
   // pass 1: 0 -> 1
-  ASL_LAUNCH(ws.prof, kKernSortHist, st, (sort_hist_kernel<false>), grid, block, 0, st, nullptr, ws.sort_key[0], T, 8, n_tiles, ws.tile_hist, ticket);
+  ASL_LAUNCH(ws.prof, kKernSortHist, st, (sort_hist_kernel<false>), grid, block, 0, st, nullptr, ws.sort_key[0], T, 8, ws.tile_hist);
   ASL_LAUNCH(ws.prof, kKernSortScatter, st, (sort_scatter_kernel<false, false>), grid, block, 0, st, nullptr, ws.sort_key[0],
                      ws.sort_idx[0], T, 8, n_tiles, ws.tile_hist, ws.sort_key[1], ws.sort_idx[1], nullptr);
   // pass 2: 1 -> 0
-  ASL_LAUNCH(ws.prof, kKernSortHist, st, (sort_hist_kernel<false>), grid, block, 0, st, nullptr, ws.sort_key[1], T, 16, n_tiles, ws.tile_hist, ticket);
+  ASL_LAUNCH(ws.prof, kKernSortHist, st, (sort_hist_kernel<false>), grid, block, 0, st, nullptr, ws.sort_key[1], T, 16, ws.tile_hist);
   ASL_LAUNCH(ws.prof, kKernSortScatter, st, (sort_scatter_kernel<false, false>), grid, block, 0, st, nullptr, ws.sort_key[1],
                      ws.sort_idx[1], T, 16, n_tiles, ws.tile_hist, ws.sort_key[0], ws.sort_idx[0], nullptr);
   // pass 3: 0 -> rank
-  ASL_LAUNCH(ws.prof, kKernSortHist, st, (sort_hist_kernel<false>), grid, block, 0, st, nullptr, ws.sort_key[0], T, 24, n_tiles, ws.tile_hist, ticket);
+  ASL_LAUNCH(ws.prof, kKernSortHist, st, (sort_hist_kernel<false>), grid, block, 0, st, nullptr, ws.sort_key[0], T, 24, ws.tile_hist);
   ASL_LAUNCH(ws.prof, kKernSortScatter, st, (sort_scatter_kernel<false, true>), grid, block, 0, st, nullptr, ws.sort_key[0],
                      ws.sort_idx[0], T, 24, n_tiles, ws.tile_hist, nullptr, nullptr, rank_out);
   return hipGetLastError();

@@ -4,25 +4,23 @@
 // Ranks are a permutation, so "the k smallest ranks of a row" is rank < k and the union over rows
 // is  min_l R[l,t] < k.  Per token the population variance times n^2 is the integer
 // n * sum R^2 - (sum R)^2; the sum over the union is accumulated exactly in 64-bit integers
-// (integer atomics: order-independent), and the workgroup that finishes last performs the single
-// double-precision division, the comparison with tau and the state update.
+// (per-workgroup partials; integer sums are order-independent), and the workgroup that finishes
+// last adds the partials and performs the single double-precision division, the comparison with
+// tau and the state update.
 #include "asl_internal.h"
 
 namespace asl {
 
 constexpr int kVarThreads = 256;
 
-__global__ void ring_push_kernel(asl_state* state, int layer_idx, int l_obs) {
+__global__ void stat_skip_kernel(asl_stat* out, asl_state* state, int layer_idx, int l_obs, int push) {
   if (threadIdx.x != 0 || blockIdx.x != 0) return;
-  int n = state->n_valid_rows;
-  if (n > 0 && state->last_layer + 1 != layer_idx) n = 0;   // not the next layer: new sequence
-  n = n + 1 < l_obs ? n + 1 : l_obs;
-  state->n_valid_rows = n;
-  state->last_layer = layer_idx;
-}
-
-__global__ void stat_skip_kernel(asl_stat* out) {
-  if (threadIdx.x != 0 || blockIdx.x != 0) return;
+  if (push) {
+    int n = state->n_valid_rows;
+    if (n > 0 && state->last_layer + 1 != layer_idx) n = 0;   // not the next layer: new sequence
+    state->n_valid_rows = n + 1 < l_obs ? n + 1 : l_obs;
+    state->last_layer = layer_idx;
+  }
   out->var_top = __builtin_nan("");
   out->rel_var = __builtin_nan("");
   out->numerator = 0;
@@ -32,42 +30,44 @@ __global__ void stat_skip_kernel(asl_stat* out) {
   out->selected = 0;
 }
 
+// Rows in use after (optionally) pushing this layer's row: a pure function of the old state, so
+// every workgroup derives it on its own; only the last workgroup writes the state back.
+__device__ __forceinline__ int rows_in_use(const asl_state* state, int layer_idx, int l_obs, int push) {
+  int n = state->n_valid_rows;
+  if (push) {
+    if (n > 0 && state->last_layer + 1 != layer_idx) n = 0;
+    n = n + 1 < l_obs ? n + 1 : l_obs;
+  }
+  return n;
+}
+
 __global__ void __launch_bounds__(kVarThreads)
 rankvar_kernel(const int32_t* __restrict__ ring, int l_obs, int T, int layer_idx, int k, double tau,
-               asl_state* state, asl_stat* out, uint32_t* counters) {
+               int push, asl_state* state, asl_stat* out, uint32_t* counters,
+               unsigned long long* __restrict__ part_num, uint32_t* __restrict__ part_cnt) {
   __shared__ unsigned long long red_num[kVarThreads / 64];
   __shared__ uint32_t red_cnt[kVarThreads / 64];
   __shared__ int is_last;
   const int tid = threadIdx.x;
-  const int n = state->n_valid_rows;                 // uniform; only the last workgroup changes it
-  if (n < 2) {
-    if (blockIdx.x == 0 && tid == 0) {
-      out->var_top = __builtin_nan("");
-      out->rel_var = __builtin_nan("");
-      out->numerator = 0;
-      out->union_size = 0;
-      out->n_rows = n;
-      out->evaluated = 0;
-      out->selected = 0;
-    }
-    return;
-  }
+  const int n = rows_in_use(state, layer_idx, l_obs, push);
   unsigned long long num = 0;
   uint32_t cnt = 0;
-  for (int t = blockIdx.x * kVarThreads + tid; t < T; t += gridDim.x * kVarThreads) {
-    unsigned long long s1 = 0, s2 = 0;
-    int mn = 0x7fffffff;
-    for (int j = 0; j < n; ++j) {
-      int row = (layer_idx - j) % l_obs;
-      if (row < 0) row += l_obs;
-      int r = ring[(int64_t)row * T + t];
-      s1 += (unsigned long long)r;
-      s2 += (unsigned long long)r * (unsigned long long)r;
-      mn = r < mn ? r : mn;
-    }
-    if (mn < k) {
-      num += (unsigned long long)n * s2 - s1 * s1;
-      cnt += 1;
+  if (n >= 2) {
+    for (int t = blockIdx.x * kVarThreads + tid; t < T; t += gridDim.x * kVarThreads) {
+      unsigned long long s1 = 0, s2 = 0;
+      int mn = 0x7fffffff;
+      for (int j = 0; j < n; ++j) {
+        int row = (layer_idx - j) % l_obs;
+        if (row < 0) row += l_obs;
+        int r = ring[(int64_t)row * T + t];
+        s1 += (unsigned long long)r;
+        s2 += (unsigned long long)r * (unsigned long long)r;
+        mn = r < mn ? r : mn;
+      }
+      if (mn < k) {
+        num += (unsigned long long)n * s2 - s1 * s1;
+        cnt += 1;
+      }
     }
   }
   for (int o = 32; o > 0; o >>= 1) {
@@ -86,20 +86,55 @@ rankvar_kernel(const int32_t* __restrict__ ring, int l_obs, int T, int layer_idx
       bn += red_num[w];
       bc += red_cnt[w];
     }
-    unsigned long long* acc_num = reinterpret_cast<unsigned long long*>(counters + kCntVarNumLo);
-    __hip_atomic_fetch_add(acc_num, bn, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    __hip_atomic_fetch_add(counters + kCntVarCount, bc, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    part_num[blockIdx.x] = bn;
+    part_cnt[blockIdx.x] = bc;
     __threadfence();
     uint32_t t = __hip_atomic_fetch_add(counters + kCntVarTicket, 1u, __ATOMIC_ACQ_REL,
                                         __HIP_MEMORY_SCOPE_AGENT);
     is_last = (t == gridDim.x - 1);
   }
   __syncthreads();
-  if (!is_last || tid != 0) return;
+  if (!is_last) return;
   __threadfence();
-  unsigned long long* acc_num = reinterpret_cast<unsigned long long*>(counters + kCntVarNumLo);
-  const unsigned long long total = __hip_atomic_load(acc_num, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  const uint32_t m = __hip_atomic_load(counters + kCntVarCount, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  // the last workgroup: fixed-order sum of the partials (integers: any order gives the same sum)
+  unsigned long long total = 0;
+  uint32_t m = 0;
+  for (int b = tid; b < (int)gridDim.x; b += kVarThreads) {
+    total += part_num[b];
+    m += part_cnt[b];
+  }
+  for (int o = 32; o > 0; o >>= 1) {
+    total += __shfl_down(total, o);
+    m += __shfl_down(m, o);
+  }
+  __syncthreads();
+  if ((tid & 63) == 0) {
+    red_num[tid >> 6] = total;
+    red_cnt[tid >> 6] = m;
+  }
+  __syncthreads();
+  if (tid != 0) return;
+  total = 0;
+  m = 0;
+  for (int w = 0; w < kVarThreads / 64; ++w) {
+    total += red_num[w];
+    m += red_cnt[w];
+  }
+  counters[kCntVarTicket] = 0;
+  if (push) {
+    state->n_valid_rows = n;
+    state->last_layer = layer_idx;
+  }
+  if (n < 2) {
+    out->var_top = __builtin_nan("");
+    out->rel_var = __builtin_nan("");
+    out->numerator = 0;
+    out->union_size = 0;
+    out->n_rows = n;
+    out->evaluated = 0;
+    out->selected = 0;
+    return;
+  }
   // var_top = numerator / (n^2 * |union|): one rounding of the integer, one division
   const double den = (double)((unsigned long long)n * (unsigned long long)n * (unsigned long long)m);
   const double var_top = (m > 0) ? (double)total / den : __builtin_nan("");
@@ -119,27 +154,21 @@ rankvar_kernel(const int32_t* __restrict__ ring, int l_obs, int T, int layer_idx
   out->evaluated = 1;
   out->selected = selected;
   if (selected) state->n_valid_rows = 0;             // release the rank cache
-  __hip_atomic_store(acc_num, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  __hip_atomic_store(counters + kCntVarCount, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  __hip_atomic_store(counters + kCntVarTicket, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-hipError_t launch_ring_push(Prof* prof, asl_state* state, int layer_idx, int l_obs, hipStream_t st) {
-  ASL_LAUNCH(prof, kKernRingPush, st, ring_push_kernel, dim3(1), dim3(64), 0, st, state, layer_idx, l_obs);
-  return hipGetLastError();
-}
-
-hipError_t launch_stat_skip(Prof* prof, asl_stat* out, hipStream_t st) {
-  ASL_LAUNCH(prof, kKernRingPush, st, stat_skip_kernel, dim3(1), dim3(64), 0, st, out);
+hipError_t launch_stat_skip(Prof* prof, asl_stat* out, asl_state* state, int layer_idx, int l_obs,
+                            int push, hipStream_t st) {
+  ASL_LAUNCH(prof, kKernRingPush, st, stat_skip_kernel, dim3(1), dim3(64), 0, st, out, state, layer_idx,
+             l_obs, push);
   return hipGetLastError();
 }
 
 hipError_t launch_rankvar(const Workspace& ws, const int32_t* ring, int l_obs, int T, int layer_idx,
-                          int k, double tau, asl_state* state, asl_stat* out, hipStream_t st) {
-  int blocks = (T + kVarThreads - 1) / kVarThreads;
-  if (blocks > 512) blocks = 512;
-  ASL_LAUNCH(ws.prof, kKernRankvar, st, rankvar_kernel, dim3(blocks), dim3(kVarThreads), 0, st, ring, l_obs, T, layer_idx, k,
-                     tau, state, out, ws.counters);
+                          int k, double tau, int push, asl_state* state, asl_stat* out, hipStream_t st) {
+  int blocks = (T + kVarThreads * 4 - 1) / (kVarThreads * 4);
+  if (blocks > kVarMaxBlocks) blocks = kVarMaxBlocks;
+  ASL_LAUNCH(ws.prof, kKernRankvar, st, rankvar_kernel, dim3(blocks), dim3(kVarThreads), 0, st, ring, l_obs,
+             T, layer_idx, k, tau, push, state, out, ws.counters, ws.var_part_num, ws.var_part_cnt);
   return hipGetLastError();
 }
 

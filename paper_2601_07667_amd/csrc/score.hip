@@ -149,17 +149,32 @@ score_rowstats_kernel(const __bf16* __restrict__ q_obs, const __bf16* __restrict
 }
 
 // Fold the per-chunk partials of every row into one log2-domain offset  m + log2(Z).
-__global__ void score_combine_kernel(const float* __restrict__ row_part, int Hk, int M, int n_chunks,
-                                     float* __restrict__ row_const) {
-  int r = blockIdx.x * blockDim.x + threadIdx.x;
+// One wavefront per row: lanes stride over the chunks, then a fixed-order butterfly.
+__global__ void __launch_bounds__(256)
+score_combine_kernel(const float* __restrict__ row_part, int Hk, int M, int n_chunks,
+                     float* __restrict__ row_const) {
+  const int lane = threadIdx.x & 63;
+  const int r = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (r >= Hk * M) return;
-  int g = r / M, row = r % M;
-  const float* p = row_part + ((int64_t)g * n_chunks * M + row) * 2;
-  float m = kNegBig;
-  for (int c = 0; c < n_chunks; ++c) m = fmaxf(m, p[(int64_t)c * M * 2]);
-  float z = 0.f;
-  for (int c = 0; c < n_chunks; ++c) z += p[(int64_t)c * M * 2 + 1] * exp2f(p[(int64_t)c * M * 2] - m);
-  row_const[r] = m + log2f(z);
+  const int g = r / M, row = r % M;
+  const float2* p = reinterpret_cast<const float2*>(row_part) + (int64_t)g * n_chunks * M + row;
+  float m = kNegBig, z = 0.f;
+  for (int c = lane; c < n_chunks; c += 64) {
+    const float2 v = p[(int64_t)c * M];
+    const float mn = fmaxf(m, v.x);
+    z = z * exp2f(m - mn) + v.y * exp2f(v.x - mn);
+    m = mn;
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    const float mo = __shfl_xor(m, o), zo = __shfl_xor(z, o);
+    const float mn = fmaxf(m, mo);
+    // add the two partial sums in lane order so both partners compute the same bits
+    const float za = z * exp2f(m - mn), zb = zo * exp2f(mo - mn);
+    z = (lane & o) ? (zb + za) : (za + zb);
+    m = mn;
+  }
+  if (lane == 0) row_const[r] = m + log2f(z);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -327,7 +342,7 @@ static hipError_t launch_score_mfma(const asl_params& p, const Workspace& ws, co
                        p.k_stride_head, p.k_stride_tok, Hk, M, p.window, N, tpc1, n_chunks, c1,
                        ws.row_part);
     const int rows = Hk * M;
-    ASL_LAUNCH(ws.prof, kKernCombine, st, score_combine_kernel, dim3((rows + 255) / 256), dim3(256), 0, st, ws.row_part,
+    ASL_LAUNCH(ws.prof, kKernCombine, st, score_combine_kernel, dim3((rows + 3) / 4), dim3(256), 0, st, ws.row_part,
                        Hk, M, n_chunks, ws.row_const);
   }
   const int n_tiles2 = (T + KT - 1) / KT;
