@@ -4,8 +4,7 @@
 One "step" = the whole hot path for one layer of the headline workload (8B shape, 128K context,
 window 32, pool 7, budget 2048) with inputs resident in HBM: asl_score_layer (two passes over K:
 row statistics + column sums, then pooling), asl_rank_stat (RankDesc into the ring + the rank-
-variance statistic over a full 8-row ring), asl_select_topk per KV head, asl_gather_kv of K and V,
-and asl_select_topk on the all-head scores.  Prints ONE JSON line.
+variance statistic over a full 8-row ring), asl_select_topk on the Hk per-head rows and the all-head row, and asl_gather_kv of K and V.  Prints ONE JSON line.
 
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2|3|5] [--lse] [--no-cpu]
 """
@@ -33,6 +32,7 @@ def main() -> int:
     ap.add_argument("--config", type=int, default=3, choices=[2, 3, 5])
     ap.add_argument("--lse", action="store_true", help="hand the rows' log-sum-exp to the scorer (one K pass)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing leg")
+    ap.add_argument("--eager", action="store_true", help="time eager launches instead of HIP-graph replay")
     ap.add_argument("--breakdown", action="store_true", help="also time every kernel with events (untimed extra loop)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -50,17 +50,18 @@ def main() -> int:
     dev = torch.device("cuda:0")
     L = synth.config_layer(args.config)
     sh = L.shape
-    ctx = asl.Asl(sh.N, sh.Hk, sh.Hq * sh.W)
+    ctx = asl.Asl(sh.N, sh.Hk + 1, sh.Hq * sh.W)
     p = asl.make_params(sh.Hq, sh.Hk, sh.d, sh.N, sh.W, sh.S, sh.budget)
     up = lambda x: torch.from_numpy(x).to(dev).to(torch.bfloat16).contiguous()
     q, k, v = up(L.q_obs), up(L.k), up(L.v)
     T, n_idx = sh.T, sh.k + sh.W
-    P = torch.empty((sh.Hk, T), dtype=torch.float32, device=dev)
-    s = torch.empty((T,), dtype=torch.float32, device=dev)
+    # P [Hk,T] and s [T] share one allocation so that one top-k call covers the Hk per-head rows
+    # (Alg. 1) and the all-head row (Alg. 2) together
+    PS = torch.empty((sh.Hk + 1, T), dtype=torch.float32, device=dev)
+    P, s = PS[:sh.Hk], PS[sh.Hk]
     ring = torch.zeros((sh.L_obs, T), dtype=torch.int32, device=dev)
     state, stat = asl.new_state(dev), asl.new_stat(dev)
-    I_head = torch.empty((sh.Hk, n_idx), dtype=torch.int32, device=dev)
-    I_all = torch.empty((1, n_idx), dtype=torch.int32, device=dev)
+    I = torch.empty((sh.Hk + 1, n_idx), dtype=torch.int32, device=dev)   # rows 0..Hk-1 per head, row Hk all-head
     Kc = torch.empty((sh.Hk, n_idx, sh.d), dtype=torch.bfloat16, device=dev)
     Vc = torch.empty_like(Kc)
     lse = None
@@ -83,30 +84,69 @@ def main() -> int:
     def step(layer_idx: int) -> None:
         ctx.asl_score_layer(p, q, k, P, s, lse=lse)
         ctx.asl_rank_stat(p, s, layer_idx, 0, sh.L_obs, 0.0, ring, state, stat)
-        ctx.asl_select_topk(p, P, sh.Hk, I_head)
-        ctx.asl_gather_kv(p, k, v, I_head, sh.Hk, n_idx, Kc, Vc)
-        ctx.asl_select_topk(p, s, 1, I_all)
+        ctx.asl_select_topk(p, PS, sh.Hk + 1, I)
+        ctx.asl_gather_kv(p, k, v, I, sh.Hk, n_idx, Kc, Vc)
 
     for _ in range(args.warmup):
         step(layer)
         layer += 1
     torch.cuda.synchronize()
 
-    # Timed region: exactly `steps` steps; HIP events (on the launch stream, recorded inside the
-    # library) bracket the dominant kernel, the pass-2 column-sum kernel, in every step.
+    # Timed region: exactly `steps` steps.  By default the steps are replayed from a HIP graph that
+    # holds L_obs consecutive layers (one trip round the rank ring), which takes the host's launch
+    # cost out of the measurement; --eager launches every kernel from Python instead.
+    use_graph = not args.eager
+    if use_graph and args.steps % sh.L_obs != 0:
+        print(f"bench.py: with graph replay --steps must be a multiple of L_obs={sh.L_obs}", file=sys.stderr)
+        return 2
+    if use_graph:
+        layer = ((layer + sh.L_obs - 1) // sh.L_obs) * sh.L_obs      # graph starts on ring row 0
+        cap_stream = torch.cuda.Stream()
+        cap_stream.wait_stream(torch.cuda.current_stream())
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(cap_stream):
+            # bring the ring in phase with the graph's first layer, then capture one trip
+            while asl.read_struct(state, asl.AslState).last_layer % sh.L_obs != sh.L_obs - 1:
+                nxt = asl.read_struct(state, asl.AslState).last_layer + 1
+                step(nxt)
+                torch.cuda.synchronize()
+            with torch.cuda.graph(graph, stream=cap_stream):
+                for j in range(sh.L_obs):
+                    step(layer + j)
+            for _ in range(2):
+                graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps // sh.L_obs):
+            graph.replay()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+    else:
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            step(layer)
+            layer += 1
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+    st = asl.read_struct(stat, asl.AslStat)
+    assert st.evaluated == 1 and st.n_rows == sh.L_obs, "statistic was not evaluated over a full ring"
+
+    # Duration of the dominant kernel (pass-2 column sums): HIP events recorded by the library on
+    # the launch stream around that kernel alone, in an eager loop of the same `steps` steps run
+    # right after the timed region (events cannot bracket a single node of a replayed graph).
     DOM = asl.KERNEL_NAMES.index("score_colsum")
     ctx.asl_profile_enable(1 << DOM, args.steps)
+    layer = asl.read_struct(state, asl.AslState).last_layer + 1
     torch.cuda.synchronize()
-    t0 = time.perf_counter()
+    e0 = time.perf_counter()
     for _ in range(args.steps):
         step(layer)
         layer += 1
     torch.cuda.synchronize()
-    t1 = time.perf_counter()
+    e1 = time.perf_counter()
     dom_ms, dom_n = ctx.asl_profile_collect(DOM)
     ctx.asl_profile_enable(0, 0)
-    st = asl.read_struct(stat, asl.AslStat)
-    assert st.evaluated == 1 and st.n_rows == sh.L_obs, "statistic was not evaluated over a full ring"
+    eager_ms_per_step = (e1 - e0) * 1e3 / args.steps
 
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     tokens_per_s = sh.N / (ms_per_step * 1e-3)
@@ -121,6 +161,7 @@ def main() -> int:
     roofline = {"bound": "hbm", "kernel": "score_colsum_kernel (pass 2)", "achieved": round(dom_gbs, 1),
                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(dom_gbs / HBM_PEAK_GBS, 4),
                 "traffic": None, "avg_launch_ms": round(dom_avg_ms, 5), "launches": dom_n,
+                "timing": "HIP events around this kernel, eager loop of the same steps after the timed region",
                 "algorithmic_bytes": dom_bytes,
                 "mfma_tflops": round(useful_flops / (dom_avg_ms * 1e-3) / 1e12, 1),
                 "mfma_frac_of_bf16_peak": round(useful_flops / (dom_avg_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4)}
@@ -151,7 +192,7 @@ def main() -> int:
         reps, t_cpu = 0, 0.0
         ost = orc.SelectState.new(sh.L_obs)
         rng = np.random.default_rng(0)
-        while t_cpu < 10.0 and reps < 8:                     # bounded sample: whole layers, ~10-30 s
+        while t_cpu < 12.0 and reps < 40:                     # bounded sample: whole layers, ~10-30 s
             c0 = time.perf_counter()
             out = orc.get_ranks(L.q_obs, L.k, L.v, sh.W, sh.S, sh.budget)
             ost.push(reps, out["rank"])
@@ -176,7 +217,9 @@ def main() -> int:
         "config": {"workload": workload[args.config], "seq_len": sh.N, "window": sh.W, "pool_kernel": sh.S,
                    "budget": sh.budget, "L_obs": sh.L_obs,
                    "score_mode": "lse supplied (one K pass)" if args.lse else "self-contained (two K passes)",
-                   "step": "score_layer + rank_stat(full ring) + select_topk(Hk rows) + gather_kv(K,V) + select_topk(1 row)"},
+                   "launch": "HIP graph replay (8 layers per graph)" if use_graph else "eager launches from Python",
+                   "eager_ms_per_step": round(eager_ms_per_step, 5),
+                   "step": "score_layer + rank_stat(full ring) + select_topk(Hk per-head rows + the all-head row) + gather_kv(K,V per head)"},
         "roofline": roofline, "cpu_baseline": cpu,
     }
     if kernels is not None:

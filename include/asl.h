@@ -132,8 +132,9 @@ asl_status asl_rankvar(asl_ctx* ctx, const int32_t* rank_ring, int32_t l_obs, in
                        int32_t layer_idx, int32_t l_min, int32_t k, double tau,
                        asl_state* state, asl_stat* out, void* stream);
 
-/* Alg. 1 step 11 + Alg. 2: rank s_all into ring row layer_idx % l_obs (a layer index that does
- * not follow state->last_layer restarts the ring), then the statistic as asl_rankvar with
+/* Alg. 1 step 11 + Alg. 2: rank s_all into ring row layer_idx % l_obs (a layer index whose ring
+ * row is not the one after state->last_layer's restarts the ring; zero the state to start a new
+ * sequence), then the statistic as asl_rankvar with
  * k = min(budget - W, T).  The host reads *out after synchronising the stream. */
 asl_status asl_rank_stat(asl_ctx* ctx, const asl_params* params, const float* s_all,
                          int32_t layer_idx, int32_t l_min, int32_t l_obs, double tau,
@@ -156,8 +157,9 @@ asl_status asl_gather_kv(asl_ctx* ctx, const asl_params* params, const void* k, 
 
 /* Measurement aid (not a step of the paper's method; for callers that time the kernels of the
  * calls above).  Kernel ids: 0 score row statistics (pass 1), 1 its combine, 2 score column sums
- * (pass 2), 3 pool, 4 sort histogram, 5 sort scatter, 6 ring push / skip, 7 rank variance,
- * 8 select histogram, 9 select count, 10 select write, 11 gather, 12 plain-FMA score kernels.
+ * (pass 2), 3 pool, 4 sort histogram, 5 sort scatter, 6 rank-variance finalisation (or the
+ * below-L_min skip), 7 rank-variance partial sums, 8 select histogram, 9 unused, 10 select write,
+ * 11 gather, 12 plain-FMA score kernels.
  * asl_profile_enable: launches whose id bit is set in kernel_mask are bracketed by HIP events on
  *   the call's stream, up to max_records launches (further ones run unrecorded); mask 0 turns
  *   it off and frees the events.  Allocates host memory and events: not for the hot loop.

@@ -174,7 +174,7 @@ class Asl:
 
 
 KERNEL_NAMES = ["score_rowstats", "score_combine", "score_colsum", "pool", "sort_hist", "sort_scatter",
-                "ring_push", "rankvar", "select_hist", "select_count", "select_write", "gather",
+                "rankvar_final", "rankvar", "select_hist", "select_count", "select_write", "gather",
                 "score_generic"]
 
 

@@ -70,10 +70,9 @@ constexpr int kSortTile = 2048;        // elements per radix-sort workgroup tile
 constexpr int kSelTile = 4096;         // elements per select workgroup tile
 constexpr int kMaxChunks = 256;        // key chunks per KV head in scoring pass 1
 constexpr int kCounterWords = 64;
-constexpr int kVarMaxBlocks = 128;     // workgroups of the rank-variance kernel
+constexpr int kVarMaxBlocks = 512;     // workgroups of the rank-variance kernel
 
 // counters layout (uint32 words)
-constexpr int kCntVarTicket = 1;
 
 hipError_t launch_score(const asl_params& p, const Workspace& ws, const void* q_obs, const void* k,
                         const float* lse, hipStream_t st);

@@ -24,12 +24,21 @@ pool_kernel(const float* __restrict__ u, int rows, int T, int S, float* __restri
   for (int row0 = 0; row0 < rows; row0 += kPoolRows) {
     const int nr = min(kPoolRows, rows - row0);
     __syncthreads();                                   // previous group's reads are done
-    for (int r = 0; r < nr; ++r) {
-      const float* ur = u + (int64_t)(row0 + r) * T;
-      for (int i = threadIdx.x; i < span; i += kPoolBlock) {
-        const int src = base - h + i;
-        tile[r][i] = (src >= 0 && src < T) ? ur[src] : 0.f;     // zero padding
-      }
+    // all loads of the group are issued before the first LDS store (span <= 2 * kPoolBlock)
+    float v0[kPoolRows], v1[kPoolRows];
+    const int src0 = base - h + threadIdx.x, src1 = src0 + kPoolBlock;
+    const bool in0 = src0 >= 0 && src0 < T;
+    const bool in1 = threadIdx.x + kPoolBlock < span && src1 >= 0 && src1 < T;
+#pragma unroll
+    for (int r = 0; r < kPoolRows; ++r) {
+      const float* ur = u + (int64_t)(row0 + min(r, nr - 1)) * T;
+      v0[r] = in0 ? ur[src0] : 0.f;                    // zero padding
+      v1[r] = in1 ? ur[src1] : 0.f;
+    }
+#pragma unroll
+    for (int r = 0; r < kPoolRows; ++r) {
+      tile[r][threadIdx.x] = v0[r];
+      if (threadIdx.x + kPoolBlock < span) tile[r][threadIdx.x + kPoolBlock] = v1[r];
     }
     __syncthreads();
     if (t < T) {

@@ -33,13 +33,17 @@ sort_hist_kernel(const float* __restrict__ s, const uint32_t* __restrict__ keys_
   h[tid] = 0;
   __syncthreads();
   const int base = blockIdx.x * kSortTile;
+  uint32_t key[kSortRounds];
+#pragma unroll
+  for (int i = 0; i < kSortRounds; ++i) {              // all loads in flight before the first use
+    const int e = base + i * kSortThreads + tid;
+    key[i] = 0;
+    if (e < T) key[i] = FIRST ? desc_key(s[e]) : keys_in[e];
+  }
 #pragma unroll
   for (int i = 0; i < kSortRounds; ++i) {
-    int e = base + i * kSortThreads + tid;
-    if (e < T) {
-      uint32_t key = FIRST ? desc_key(s[e]) : keys_in[e];
-      atomicAdd(&h[(key >> shift) & 255u], 1u);
-    }
+    const int e = base + i * kSortThreads + tid;
+    if (e < T) atomicAdd(&h[(key[i] >> shift) & 255u], 1u);
   }
   __syncthreads();
   tile_hist[(int64_t)blockIdx.x * 256 + tid] = h[tid];
@@ -62,16 +66,35 @@ sort_scatter_kernel(const float* __restrict__ s, const uint32_t* __restrict__ ke
 #pragma unroll
   for (int w = 0; w < kSortWaves; ++w) cnt[w][tid] = 0;
 
+  // this wave's elements: issue every load before anything waits on one
+  constexpr int R = kSortPerWave / 64;
+  uint32_t key[R], idx[R], off[R];
+  const int base = blockIdx.x * kSortTile + wave * kSortPerWave;
+#pragma unroll
+  for (int r = 0; r < R; ++r) {
+    const int e = base + r * 64 + lane;
+    key[r] = 0;
+    idx[r] = 0;
+    if (e < T) {
+      key[r] = FIRST ? desc_key(s[e]) : keys_in[e];
+      idx[r] = FIRST ? (uint32_t)e : idx_in[e];
+    }
+  }
+
   // digit `tid`: total over all tiles and over the tiles before this one
   uint32_t tot = 0, prev = 0;
   {
     const int me = blockIdx.x;
     int t = 0;
-    for (; t + 4 <= n_tiles; t += 4) {
-      uint32_t v0 = tile_hist[(int64_t)(t + 0) * 256 + tid], v1 = tile_hist[(int64_t)(t + 1) * 256 + tid];
-      uint32_t v2 = tile_hist[(int64_t)(t + 2) * 256 + tid], v3 = tile_hist[(int64_t)(t + 3) * 256 + tid];
-      tot += v0 + v1 + v2 + v3;
-      prev += (t + 0 < me ? v0 : 0u) + (t + 1 < me ? v1 : 0u) + (t + 2 < me ? v2 : 0u) + (t + 3 < me ? v3 : 0u);
+    for (; t + 8 <= n_tiles; t += 8) {
+      uint32_t v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) v[u] = tile_hist[(int64_t)(t + u) * 256 + tid];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        tot += v[u];
+        prev += (t + u < me) ? v[u] : 0u;
+      }
     }
     for (; t < n_tiles; ++t) {
       uint32_t v = tile_hist[(int64_t)t * 256 + tid];
@@ -92,20 +115,11 @@ sort_scatter_kernel(const float* __restrict__ s, const uint32_t* __restrict__ ke
   for (int w = 0; w < wave; ++w) digit_base += wave_sum[w];
   const uint32_t my_off = digit_base + prev;         // first destination of digit `tid` in this tile
 
-  constexpr int R = kSortPerWave / 64;
-  uint32_t key[R], idx[R], off[R];
-  const int base = blockIdx.x * kSortTile + wave * kSortPerWave;
   const uint64_t lt_mask = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
 #pragma unroll
   for (int r = 0; r < R; ++r) {
     const int e = base + r * 64 + lane;
     const bool valid = e < T;
-    key[r] = 0;
-    idx[r] = 0;
-    if (valid) {
-      key[r] = FIRST ? desc_key(s[e]) : keys_in[e];
-      idx[r] = FIRST ? (uint32_t)e : idx_in[e];
-    }
     const uint32_t d = (key[r] >> shift) & 255u;
     uint64_t peers = __ballot(valid);
 #pragma unroll

@@ -4,9 +4,9 @@
 // Ranks are a permutation, so "the k smallest ranks of a row" is rank < k and the union over rows
 // is  min_l R[l,t] < k.  Per token the population variance times n^2 is the integer
 // n * sum R^2 - (sum R)^2; the sum over the union is accumulated exactly in 64-bit integers
-// (per-workgroup partials; integer sums are order-independent), and the workgroup that finishes
-// last adds the partials and performs the single double-precision division, the comparison with
-// tau and the state update.
+// (per-workgroup partials; integer sums are order-independent); a second one-workgroup kernel adds
+// the partials and performs the single double-precision division, the comparison with tau and the
+// state update.  No atomics, no fences.
 #include "asl_internal.h"
 
 namespace asl {
@@ -17,7 +17,7 @@ __global__ void stat_skip_kernel(asl_stat* out, asl_state* state, int layer_idx,
   if (threadIdx.x != 0 || blockIdx.x != 0) return;
   if (push) {
     int n = state->n_valid_rows;
-    if (n > 0 && state->last_layer + 1 != layer_idx) n = 0;   // not the next layer: new sequence
+    if (n > 0 && (state->last_layer + 1) % l_obs != layer_idx % l_obs) n = 0;   // not the next ring row
     state->n_valid_rows = n + 1 < l_obs ? n + 1 : l_obs;
     state->last_layer = layer_idx;
   }
@@ -35,31 +35,35 @@ __global__ void stat_skip_kernel(asl_stat* out, asl_state* state, int layer_idx,
 __device__ __forceinline__ int rows_in_use(const asl_state* state, int layer_idx, int l_obs, int push) {
   int n = state->n_valid_rows;
   if (push) {
-    if (n > 0 && state->last_layer + 1 != layer_idx) n = 0;
+    if (n > 0 && (state->last_layer + 1) % l_obs != layer_idx % l_obs) n = 0;   // not the next ring row
     n = n + 1 < l_obs ? n + 1 : l_obs;
   }
   return n;
 }
 
+// Kernel 1: per-workgroup partial sums over the union (no atomics; integers, so the order of the
+// later addition does not matter).
 __global__ void __launch_bounds__(kVarThreads)
-rankvar_kernel(const int32_t* __restrict__ ring, int l_obs, int T, int layer_idx, int k, double tau,
-               int push, asl_state* state, asl_stat* out, uint32_t* counters,
-               unsigned long long* __restrict__ part_num, uint32_t* __restrict__ part_cnt) {
+rankvar_partial_kernel(const int32_t* __restrict__ ring, int l_obs, int T, int layer_idx, int k, int push,
+                       const asl_state* __restrict__ state, unsigned long long* __restrict__ part_num,
+                       uint32_t* __restrict__ part_cnt) {
   __shared__ unsigned long long red_num[kVarThreads / 64];
   __shared__ uint32_t red_cnt[kVarThreads / 64];
-  __shared__ int is_last;
   const int tid = threadIdx.x;
   const int n = rows_in_use(state, layer_idx, l_obs, push);
   unsigned long long num = 0;
   uint32_t cnt = 0;
   if (n >= 2) {
+    int row0 = (layer_idx - (n - 1)) % l_obs;            // oldest row in use
+    if (row0 < 0) row0 += l_obs;
     for (int t = blockIdx.x * kVarThreads + tid; t < T; t += gridDim.x * kVarThreads) {
       unsigned long long s1 = 0, s2 = 0;
       int mn = 0x7fffffff;
+      int row = row0;
+#pragma unroll 8
       for (int j = 0; j < n; ++j) {
-        int row = (layer_idx - j) % l_obs;
-        if (row < 0) row += l_obs;
-        int r = ring[(int64_t)row * T + t];
+        const int r = ring[(int64_t)row * T + t];
+        row = (row + 1 == l_obs) ? 0 : row + 1;
         s1 += (unsigned long long)r;
         s2 += (unsigned long long)r * (unsigned long long)r;
         mn = r < mn ? r : mn;
@@ -88,18 +92,21 @@ rankvar_kernel(const int32_t* __restrict__ ring, int l_obs, int T, int layer_idx
     }
     part_num[blockIdx.x] = bn;
     part_cnt[blockIdx.x] = bc;
-    __threadfence();
-    uint32_t t = __hip_atomic_fetch_add(counters + kCntVarTicket, 1u, __ATOMIC_ACQ_REL,
-                                        __HIP_MEMORY_SCOPE_AGENT);
-    is_last = (t == gridDim.x - 1);
   }
-  __syncthreads();
-  if (!is_last) return;
-  __threadfence();
-  // the last workgroup: fixed-order sum of the partials (integers: any order gives the same sum)
+}
+
+// Kernel 2 (one workgroup): add the partials, one division, the comparison with tau, state update.
+__global__ void __launch_bounds__(kVarThreads)
+rankvar_final_kernel(int n_parts, int l_obs, int layer_idx, double tau, int push, asl_state* state,
+                     asl_stat* out, const unsigned long long* __restrict__ part_num,
+                     const uint32_t* __restrict__ part_cnt) {
+  __shared__ unsigned long long red_num[kVarThreads / 64];
+  __shared__ uint32_t red_cnt[kVarThreads / 64];
+  const int tid = threadIdx.x;
+  const int n = rows_in_use(state, layer_idx, l_obs, push);
   unsigned long long total = 0;
   uint32_t m = 0;
-  for (int b = tid; b < (int)gridDim.x; b += kVarThreads) {
+  for (int b = tid; b < n_parts; b += kVarThreads) {
     total += part_num[b];
     m += part_cnt[b];
   }
@@ -107,12 +114,11 @@ rankvar_kernel(const int32_t* __restrict__ ring, int l_obs, int T, int layer_idx
     total += __shfl_down(total, o);
     m += __shfl_down(m, o);
   }
-  __syncthreads();
   if ((tid & 63) == 0) {
     red_num[tid >> 6] = total;
     red_cnt[tid >> 6] = m;
   }
-  __syncthreads();
+  __syncthreads();                                   // every thread has read the old state by now
   if (tid != 0) return;
   total = 0;
   m = 0;
@@ -120,7 +126,6 @@ rankvar_kernel(const int32_t* __restrict__ ring, int l_obs, int T, int layer_idx
     total += red_num[w];
     m += red_cnt[w];
   }
-  counters[kCntVarTicket] = 0;
   if (push) {
     state->n_valid_rows = n;
     state->last_layer = layer_idx;
@@ -165,10 +170,12 @@ hipError_t launch_stat_skip(Prof* prof, asl_stat* out, asl_state* state, int lay
 
 hipError_t launch_rankvar(const Workspace& ws, const int32_t* ring, int l_obs, int T, int layer_idx,
                           int k, double tau, int push, asl_state* state, asl_stat* out, hipStream_t st) {
-  int blocks = (T + kVarThreads * 4 - 1) / (kVarThreads * 4);
+  int blocks = (T + kVarThreads - 1) / kVarThreads;
   if (blocks > kVarMaxBlocks) blocks = kVarMaxBlocks;
-  ASL_LAUNCH(ws.prof, kKernRankvar, st, rankvar_kernel, dim3(blocks), dim3(kVarThreads), 0, st, ring, l_obs,
-             T, layer_idx, k, tau, push, state, out, ws.counters, ws.var_part_num, ws.var_part_cnt);
+  ASL_LAUNCH(ws.prof, kKernRankvar, st, rankvar_partial_kernel, dim3(blocks), dim3(kVarThreads), 0, st, ring,
+             l_obs, T, layer_idx, k, push, state, ws.var_part_num, ws.var_part_cnt);
+  ASL_LAUNCH(ws.prof, kKernRingPush, st, rankvar_final_kernel, dim3(1), dim3(kVarThreads), 0, st, blocks, l_obs,
+             layer_idx, tau, push, state, out, ws.var_part_num, ws.var_part_cnt);
   return hipGetLastError();
 }
 

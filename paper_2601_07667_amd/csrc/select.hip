@@ -42,12 +42,25 @@ struct Pick {
 __device__ __forceinline__ Pick pick_digit(const uint32_t* __restrict__ hp, int n_tiles, int me,
                                            uint32_t k_rem_in, uint32_t* sm /* >= 16 words */) {
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-  uint32_t tot = 0, prev = 0, mine = 0;
-  for (int t = 0; t < n_tiles; ++t) {
+  // column `tid` of the [n_tiles][256] table: all tiles, and the tiles before this one.
+  // Loads are independent; unrolled so that many are in flight at once.
+  uint32_t tot = 0, prev = 0;
+  const uint32_t mine = hp[(int64_t)me * 256 + tid];
+  int t = 0;
+  for (; t + 8 <= n_tiles; t += 8) {
+    uint32_t v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v[u] = hp[(int64_t)(t + u) * 256 + tid];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      tot += v[u];
+      prev += (t + u < me) ? v[u] : 0u;
+    }
+  }
+  for (; t < n_tiles; ++t) {
     const uint32_t v = hp[(int64_t)t * 256 + tid];
     tot += v;
     prev += (t < me) ? v : 0u;
-    mine = (t == me) ? v : mine;
   }
   uint32_t incl = tot;
 #pragma unroll
@@ -100,6 +113,15 @@ select_hist_kernel(const float* __restrict__ scores, int T, int n_tiles, int row
   __shared__ uint32_t sm[16];
   const int tid = threadIdx.x, row = blockIdx.y, tile = blockIdx.x;
   const int shift = 24 - 8 * pass;
+  const float* sr = scores + (int64_t)row * T;
+  const int base = tile * kSelTile;
+  constexpr int E = kSelTile / kSelThreads;
+  uint32_t key[E];
+#pragma unroll
+  for (int i = 0; i < E; ++i) {                        // all loads in flight before the first use
+    const int e = base + i * kSelThreads + tid;
+    key[i] = (e < T) ? sel_key(sr[e]) : 0u;
+  }
   uint32_t prefix = 0;
   if (pass > 0) {
     const uint32_t* st_in = state + ((int64_t)(pass - 1) * rows + row) * 2;
@@ -120,15 +142,11 @@ select_hist_kernel(const float* __restrict__ scores, int T, int n_tiles, int row
   }
   h[tid] = 0;
   __syncthreads();
-  const float* sr = scores + (int64_t)row * T;
-  const int base = tile * kSelTile;
-  for (int i = 0; i < kSelTile / kSelThreads; ++i) {
+#pragma unroll
+  for (int i = 0; i < E; ++i) {
     const int e = base + i * kSelThreads + tid;
-    if (e < T) {
-      const uint32_t key = sel_key(sr[e]);
-      const bool match = (pass == 0) || ((key >> (shift + 8)) == prefix);
-      if (match) atomicAdd(&h[(key >> shift) & 255u], 1u);
-    }
+    const bool match = (pass == 0) || ((key[i] >> (shift + 8)) == prefix);
+    if (e < T && match) atomicAdd(&h[(key[i] >> shift) & 255u], 1u);
   }
   __syncthreads();
   hist[(((int64_t)pass * rows + row) * n_tiles + tile) * 256 + tid] = h[tid];
@@ -143,12 +161,20 @@ select_write_kernel(const float* __restrict__ scores, int T, int n_tiles, int ro
   __shared__ uint32_t red[kSelWaves];
   __shared__ uint32_t wave_tot[2][kSelWaves];
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, row = blockIdx.y, tile = blockIdx.x;
+  const float* sr = scores + (int64_t)row * T;
+  // this wave's keys (kSelPerWave consecutive tokens, 64 per round), loaded before anything waits
+  const int base = tile * kSelTile + wave * kSelPerWave;
+  uint32_t key[kSelRounds];
+#pragma unroll
+  for (int r = 0; r < kSelRounds; ++r) {
+    const int e = base + r * 64 + lane;
+    key[r] = (e < T) ? sel_key(sr[e]) : 0xffffffffu;
+  }
   const uint32_t* st_in = state + ((int64_t)3 * rows + row) * 2;          // 3-digit prefix, written by pass 3
   const uint32_t* h3 = hist + ((int64_t)3 * rows + row) * n_tiles * 256;
   const Pick p = pick_digit(h3, n_tiles, tile, st_in[1], sm);
   const uint32_t thr = (st_in[0] << 8) | p.digit;
   const uint32_t k_rem = p.k_rem;
-  const float* sr = scores + (int64_t)row * T;
   int32_t* out = idx_out + (int64_t)row * (k + W);
 
   // keys below the threshold in the tiles before this one (passes 0-2 from tile_lt, pass 3 from h3)
@@ -157,15 +183,12 @@ select_write_kernel(const float* __restrict__ scores, int T, int n_tiles, int ro
   for (int o = 32; o > 0; o >>= 1) lt_b += __shfl_down(lt_b, o);
   if (lane == 0) red[wave] = lt_b;
 
-  // this wave's keys (kSelPerWave consecutive tokens, 64 per round) and its totals
-  const int base = tile * kSelTile + wave * kSelPerWave;
-  uint32_t key[kSelRounds];
+  // this wave's totals
   uint32_t w_lt = 0, w_eq = 0;
 #pragma unroll
   for (int r = 0; r < kSelRounds; ++r) {
     const int e = base + r * 64 + lane;
     const bool v = e < T;
-    key[r] = v ? sel_key(sr[e]) : 0xffffffffu;
     w_lt += __popcll(__ballot(v && key[r] < thr));
     w_eq += __popcll(__ballot(v && key[r] == thr));
   }
