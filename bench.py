@@ -33,6 +33,8 @@ def main() -> int:
     ap.add_argument("--lse", action="store_true", help="hand the rows' log-sum-exp to the scorer (one K pass)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing leg")
     ap.add_argument("--eager", action="store_true", help="time eager launches instead of HIP-graph replay")
+    ap.add_argument("--copy-ref", action="store_true",
+                    help="also run a plain 256 MiB device copy (a reference of known traffic for counter runs)")
     ap.add_argument("--breakdown", action="store_true", help="also time every kernel with events (untimed extra loop)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -91,6 +93,14 @@ def main() -> int:
         step(layer)
         layer += 1
     torch.cuda.synchronize()
+    if args.copy_ref:
+        # 64 Mi fp32 elements = 256 MiB read + 256 MiB written by one elementwise copy kernel
+        src = torch.empty(64 * 1024 * 1024, dtype=torch.float32, device=dev).normal_()
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     # Timed region: exactly `steps` steps.  By default the steps are replayed from a HIP graph that
     # holds L_obs consecutive layers (one trip round the rank ring), which takes the host's launch

@@ -11,7 +11,7 @@ import os
 from typing import Optional
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_PKG, "libasl.so")
+LIB_PATH = os.environ.get("ASL_LIBRARY_PATH") or os.path.join(_PKG, "libasl.so")
 
 ASL_OK, ASL_EINVAL, ASL_ENOMEM, ASL_EHIP, ASL_EUNSUPPORTED = 0, -1, -2, -3, -4
 ASL_BF16, ASL_F32 = 0, 1

@@ -9,8 +9,8 @@
 //
 // Work split: a workgroup owns one KV head and a contiguous chunk of keys; wave w owns query rows
 // [32w, 32w+32) and keeps their bf16 fragments in registers for the whole kernel; K tiles of 128
-// keys are staged through LDS (coalesced 16-byte global loads, padded rows) and every wave reads
-// all of them as the other MFMA operand (v_mfma_f32_32x32x16_bf16).  Pass 1 puts keys on the
+// keys stream global -> LDS directly (double-buffered, XOR-swizzled) and every wave reads all of
+// them as the other MFMA operand (v_mfma_f32_32x32x16_bf16).  Pass 1 puts keys on the
 // accumulator's register axis (row statistics reduce in-lane), pass 2 puts query rows there
 // (column sums reduce in-lane).  All reductions have a fixed order: results are deterministic.
 #include "asl_internal.h"
@@ -20,38 +20,136 @@ namespace asl {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
-constexpr int KT = 128;                       // keys per LDS tile
+constexpr int KT = 64;                        // keys per LDS tile
+constexpr int STAGES = 3;                     // LDS tile buffers: two tiles in flight while one is consumed
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kNegBig = -1.0e30f;           // finite stand-in for "no maximum yet"
 
+#ifdef ASL_DIAG_NOEXP   // diagnosis builds only: wrong results, shows how much time the exponentials cost
+__device__ __forceinline__ float fast_exp2(float x) { return x; }
+#else
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+#endif
 
 // Row of the 32x32 accumulator held by register r of a lane in half `half` (lanes 32..63 = 1).
 __device__ __forceinline__ int acc_row(int r, int half) { return 8 * (r >> 2) + 4 * half + (r & 3); }
 
-// Global -> register staging of one K tile (KT keys x D bf16), 16 bytes per thread per step;
-// rows past N are clamped to the last key (they are masked or discarded later).
-#define ASL_KTILE_DECL(D, NT)                                                                  \
-  constexpr int CPR = (D) / 8;                          /* 16-byte pieces per key row */       \
-  constexpr int NLOAD = (KT * CPR + (NT) - 1) / (NT);   /* pieces per thread */                \
-  uint4 stage[NLOAD];
-
-#define ASL_KTILE_LOAD(key0)                                                                    \
-  _Pragma("unroll") for (int i_ = 0; i_ < NLOAD; ++i_) {                                        \
-    const int q_ = tid + i_ * NT;                                                               \
-    const int row_ = q_ / CPR, col_ = q_ % CPR;                                                 \
-    const int key_ = min((key0) + row_, N - 1);                                                 \
-    uint4 v_ = make_uint4(0u, 0u, 0u, 0u);                                                      \
-    if (q_ < KT * CPR) v_ = *reinterpret_cast<const uint4*>(kg + (int64_t)key_ * kst + col_ * 8); \
-    stage[i_] = v_;                                                                             \
+// K tile staging: global memory -> LDS directly (global_load_lds_dwordx4: each lane names its own
+// 16-byte global source, the hardware writes lane i's data to  wave base + 16*i  in LDS), two LDS
+// buffers, one workgroup barrier per tile.  The tile is stored unpadded; bank conflicts on the
+// fragment reads are avoided by an XOR swizzle applied on the global side: LDS slot (row r,
+// piece c') holds the row's 16-byte piece  c = c' ^ (r mod CPR).
+// Rows past N are clamped to the last key (they are masked or discarded later).
+// Per-thread constants of the tile loader: for each of its NLOAD pieces the tile row and the byte
+// offset of the (swizzled) source piece from the tile's first key.
+template <int D, int NT>
+struct TilePieces {
+  static constexpr int CPR = D / 8;                   // 16-byte pieces per key row
+  static constexpr int SLOTS = KT * CPR;
+  static constexpr int NLOAD = (SLOTS + NT - 1) / NT;
+  uint32_t src_off[NLOAD];
+  int row[NLOAD];
+  int col8[NLOAD];
+  __device__ __forceinline__ void init(int64_t kst, int tid) {
+#pragma unroll
+    for (int i = 0; i < NLOAD; ++i) {
+      const int q = i * NT + tid;
+      const int r = q / CPR, cp = q % CPR;
+      row[i] = r;
+      col8[i] = (cp ^ (r & (CPR - 1))) * 8;
+      src_off[i] = (uint32_t)(((int64_t)r * kst + col8[i]) * 2);
+    }
   }
+};
 
-#define ASL_KTILE_STORE()                                                                       \
-  _Pragma("unroll") for (int i_ = 0; i_ < NLOAD; ++i_) {                                        \
-    const int q_ = tid + i_ * NT;                                                               \
-    const int row_ = q_ / CPR, col_ = q_ % CPR;                                                 \
-    if (q_ < KT * CPR) *reinterpret_cast<uint4*>(lds_k + row_ * ROW + col_ * 8) = stage[i_];    \
+template <int D, int NT, bool FULL>
+__device__ __forceinline__ void issue_tile_loads_impl(const TilePieces<D, NT>& tp,
+                                                      const __bf16* __restrict__ kg, int64_t kst, int key0,
+                                                      int N, __bf16* __restrict__ lds_buf, int tid) {
+  constexpr int SLOTS = TilePieces<D, NT>::SLOTS;
+  constexpr int NLOAD = TilePieces<D, NT>::NLOAD;
+  const int wave_slot0 = __builtin_amdgcn_readfirstlane(tid) & ~63;
+  const char* tile_base = reinterpret_cast<const char*>(kg + (int64_t)key0 * kst);   // uniform
+#pragma unroll
+  for (int i = 0; i < NLOAD; ++i) {
+    if (SLOTS % NT == 0 || i * NT + tid < SLOTS) {
+      const char* src;
+      if (FULL) {
+        src = tile_base + tp.src_off[i];
+      } else {                                            // last, partial tile: clamp the row
+        const int key = min(key0 + tp.row[i], N - 1);
+        src = reinterpret_cast<const char*>(kg + (int64_t)key * kst + tp.col8[i]);
+      }
+      __bf16* dst = lds_buf + (int64_t)(i * NT + wave_slot0) * 8;     // wave-uniform base
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
+                                       (__attribute__((address_space(3))) void*)dst, 16, 0, 0);
+    }
   }
+}
+
+// Full tiles take the precomputed offsets; only a tile that reaches past N pays for clamping.
+template <int D, int NT>
+__device__ __forceinline__ void issue_tile_loads(const TilePieces<D, NT>& tp, const __bf16* __restrict__ kg,
+                                                 int64_t kst, int key0, int N, __bf16* __restrict__ lds_buf,
+                                                 int tid) {
+  if (key0 + KT <= N)
+    issue_tile_loads_impl<D, NT, true>(tp, kg, kst, key0, N, lds_buf, tid);
+  else
+    issue_tile_loads_impl<D, NT, false>(tp, kg, kst, key0, N, lds_buf, tid);
+}
+
+// Wait until at most CNT of this wave's vector-memory operations (incl. its LDS-direct loads) are
+// still outstanding; they complete in issue order, so everything older than the last CNT is done.
+template <int CNT>
+__device__ __forceinline__ void wait_vmem() {
+  static_assert(CNT >= 0 && CNT < 16, "vmcnt immediate (low 4 bits used)");
+  __builtin_amdgcn_s_waitcnt(0x0F70 | CNT);          // vmcnt(CNT), expcnt/lgkmcnt untouched
+}
+
+// Loads each wave issues per tile, when that number is the same for every wave (else -1).
+template <int D, int NT>
+constexpr int tile_loads_per_wave() { return ((KT * (D / 8)) % NT == 0) ? (KT * (D / 8)) / NT : -1; }
+
+// Top-of-iteration wait: tile `it` must have landed.  With a uniform per-wave load count the
+// younger tile (if one is in flight) may stay outstanding; otherwise wait for everything.
+template <int D, int NT>
+__device__ __forceinline__ void wait_tile(bool younger_in_flight) {
+  constexpr int L = tile_loads_per_wave<D, NT>();
+  if constexpr (L > 0 && L < 16) {
+    if (younger_in_flight) {
+      wait_vmem<L>();
+      return;
+    }
+  }
+  wait_vmem<0>();
+}
+
+// K fragment of kstep ks for the 32-key sub-tile `sub`: lane (ln, half) holds key ln,
+// d = 16*ks + 8*half .. +8  (logical piece 2*ks + half, un-swizzled here).
+template <int D>
+__device__ __forceinline__ bf16x8 load_k_frag(const __bf16* buf, int sub, int ln, int half, int ks) {
+  constexpr int CPR = D / 8;
+  const int r = sub * 32 + ln;
+  const int cp = (2 * ks + half) ^ (r & (CPR - 1));
+  return *reinterpret_cast<const bf16x8*>(buf + (r * CPR + cp) * 8);
+}
+
+// QK^T of one 32-key sub-tile against this wave's 32 query rows (d/16 chained MFMAs).
+// KEYS_ON_REGS: accumulator register axis = keys (pass 1), else = query rows (pass 2).
+template <int D, bool KEYS_ON_REGS>
+__device__ __forceinline__ f32x16 mma_subtile(const __bf16* __restrict__ buf, int sub, int ln, int half,
+                                              const bf16x8 (&qf)[D / 16]) {
+  f32x16 acc;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+#pragma unroll
+  for (int ks = 0; ks < D / 16; ++ks) {
+    const bf16x8 kf = load_k_frag<D>(buf, sub, ln, half, ks);
+    acc = KEYS_ON_REGS ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], acc, 0, 0, 0)
+                       : __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[ks], kf, acc, 0, 0, 0);
+  }
+  return acc;
+}
 
 // Query fragments of this wave's 32-row block: lane (ln, half) holds row ln, d = 16*ks + 8*half .. +8.
 #define ASL_LOAD_Q_FRAGS()                                                                      \
@@ -65,8 +163,50 @@ __device__ __forceinline__ int acc_row(int r, int half) { return 8 * (r >> 2) + 
     }                                                                                           \
   }
 
-// max without NaN canonicalisation (inputs are never NaN here; -inf is fine)
-__device__ __forceinline__ float max2(float a, float b) { return a > b ? a : b; }
+// This file is compiled with NaNs assumed absent, so this is a bare v_max_f32 / v_max3_f32
+// (inputs are finite or -inf here).
+__device__ __forceinline__ float max2(float a, float b) { return __builtin_fmaxf(a, b); }
+
+// One tile of pass 1: start the next tile's LDS-direct loads into `nxt`, then fold the tile in
+// `cur` into the running (max, sum).  The two LDS buffers are distinct restrict pointers so that
+// the compiler knows the fragment reads of `cur` need not wait for the loads into `nxt`.
+template <int D, int NT>
+__device__ __forceinline__ void rowstats_tile(const __bf16* __restrict__ cur, __bf16* __restrict__ nxt,
+                                              bool prefetch, const TilePieces<D, NT>& tp, const __bf16* __restrict__ kg, int64_t kst,
+                                              int tile, int N, int T, int wi, int tid, int ln, int half,
+                                              const bf16x8 (&qf)[D / 16], float c1, float& m_run,
+                                              float& z_run) {
+  if (prefetch) issue_tile_loads<D, NT>(tp, kg, kst, (tile + STAGES - 1) * KT, N, nxt, tid);
+  const int kbase = tile * KT;
+  const bool need_mask = (kbase + KT > T);      // touches the window block or the tail past N
+  // Software pipeline over the four 32-key sub-tiles: the MFMAs of sub-tile s+1 are issued before
+  // the softmax arithmetic of sub-tile s, so the matrix pipe and the vector ALU run side by side.
+  f32x16 acc = mma_subtile<D, true>(cur, 0, ln, half, qf);
+#pragma unroll
+  for (int sub = 0; sub < KT / 32; ++sub) {
+    f32x16 nxt_acc = acc;
+    if (sub + 1 < KT / 32) nxt_acc = mma_subtile<D, true>(cur, sub + 1, ln, half, qf);
+    float x[16];
+#pragma unroll
+    for (int r = 0; r < 16; ++r) x[r] = acc[r];
+    if (need_mask) {
+      // visible iff key < N and (key < T or key - T <= wi)  <=>  key < min(N, T + wi + 1)
+      const int lim = min(N, T + wi + 1) - (kbase + sub * 32 + 4 * half);
+#pragma unroll
+      for (int r = 0; r < 16; ++r) x[r] = (8 * (r >> 2) + (r & 3) < lim) ? x[r] : -INFINITY;
+    }
+    float mx = x[0];
+#pragma unroll
+    for (int r = 1; r < 16; r += 2) mx = max2(mx, max2(x[r], x[(r + 1) & 15]));
+    const float m_new = max2(m_run, mx * c1);
+    float sum = 0.f;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) sum += fast_exp2(fmaf(x[r], c1, -m_new));
+    z_run = z_run * fast_exp2(m_run - m_new) + sum;
+    m_run = m_new;
+    acc = nxt_acc;
+  }
+}
 
 // ---------------------------------------------------------------------------------------------
 // Pass 1: per-row running (max, sum) over this workgroup's key chunk, in the log2 domain.
@@ -77,64 +217,38 @@ score_rowstats_kernel(const __bf16* __restrict__ q_obs, const __bf16* __restrict
                       int64_t kst, int Hk, int M, int W, int N, int tiles_per_chunk, int n_chunks,
                       float c1, float* __restrict__ row_part) {
   constexpr int NT = NW * 64;
-  constexpr int ROW = D + 8;
   constexpr int KS = D / 16;
-  __shared__ __attribute__((aligned(16))) __bf16 lds_k[KT * ROW];
+  constexpr int TILE_ELEMS = KT * D;
+  __shared__ __attribute__((aligned(16))) __bf16 lds_k[STAGES * TILE_ELEMS];
 
   const int g = blockIdx.x % Hk, chunk = blockIdx.x / Hk;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, ln = lane & 31, half = lane >> 5;
   const int T = N - W;
   const int qrow = wave * 32 + ln;
   const int wi = qrow % W;                      // window row of this lane's query row
-  ASL_LOAD_Q_FRAGS();
-
   const __bf16* kg = k + (int64_t)g * ksh;
   const int n_tiles_total = (N + KT - 1) / KT;
   const int tile0 = chunk * tiles_per_chunk;
   const int tile_end = min(tile0 + tiles_per_chunk, n_tiles_total);
 
+  ASL_LOAD_Q_FRAGS();
+  TilePieces<D, NT> tp;
+  tp.init(kst, tid);
+  // prologue: STAGES-1 tiles in flight (after the Q loads, so the in-order wait counts line up)
+#pragma unroll
+  for (int j = 0; j < STAGES - 1; ++j)
+    if (tile0 + j < tile_end) issue_tile_loads<D, NT>(tp, kg, kst, (tile0 + j) * KT, N, lds_k + j * TILE_ELEMS, tid);
+
   float m_run = kNegBig, z_run = 0.f;
-  ASL_KTILE_DECL(D, NT);
-  if (tile0 < tile_end) { ASL_KTILE_LOAD(tile0 * KT); }
-
+  int stage = 0;                                  // buffer that holds tile `tile`
   for (int tile = tile0; tile < tile_end; ++tile) {
-    __syncthreads();                            // every wave is done reading the previous tile
-    ASL_KTILE_STORE();
-    __syncthreads();
-    if (tile + 1 < tile_end) { ASL_KTILE_LOAD((tile + 1) * KT); }
-
-    const int kbase = tile * KT;
-    const bool need_mask = (kbase + KT > T);    // touches the window block or the tail past N
-#pragma unroll
-    for (int sub = 0; sub < KT / 32; ++sub) {
-      f32x16 acc;
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[r] = 0.f;
-      const __bf16* krow = lds_k + (sub * 32 + ln) * ROW + half * 8;
-#pragma unroll
-      for (int ks = 0; ks < KS; ++ks) {
-        bf16x8 kf = *reinterpret_cast<const bf16x8*>(krow + ks * 16);
-        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], acc, 0, 0, 0);   // [key][query row]
-      }
-      float x[16];
-#pragma unroll
-      for (int r = 0; r < 16; ++r) x[r] = acc[r];
-      if (need_mask) {
-        // visible iff key < N and (key < T or key - T <= wi)  <=>  key < min(N, T + wi + 1)
-        const int lim = min(N, T + wi + 1) - (kbase + sub * 32 + 4 * half);
-#pragma unroll
-        for (int r = 0; r < 16; ++r) x[r] = (8 * (r >> 2) + (r & 3) < lim) ? x[r] : -INFINITY;
-      }
-      float mx = x[0];
-#pragma unroll
-      for (int r = 1; r < 16; ++r) mx = max2(mx, x[r]);
-      const float m_new = max2(m_run, mx * c1);
-      float sum = 0.f;
-#pragma unroll
-      for (int r = 0; r < 16; ++r) sum += fast_exp2(fmaf(x[r], c1, -m_new));
-      z_run = z_run * fast_exp2(m_run - m_new) + sum;
-      m_run = m_new;
-    }
+    wait_tile<D, NT>(tile + 1 < tile_end);
+    __syncthreads();      // tile `tile` has landed for every wave; the buffer of tile-1 is free again
+    const int free_stage = (stage == 0) ? STAGES - 1 : stage - 1;
+    rowstats_tile<D, NT>(lds_k + stage * TILE_ELEMS, lds_k + free_stage * TILE_ELEMS,
+                         tile + STAGES - 1 < tile_end, tp, kg, kst, tile, N, T, wi, tid, ln, half, qf, c1, m_run,
+                         z_run);
+    stage = (stage + 1 == STAGES) ? 0 : stage + 1;
   }
   // the two lane halves hold disjoint keys of the same query row
   const float m_o = __shfl_xor(m_run, 32), z_o = __shfl_xor(z_run, 32);
@@ -177,6 +291,29 @@ score_combine_kernel(const float* __restrict__ row_part, int Hk, int M, int n_ch
   if (lane == 0) row_const[r] = m + log2f(z);
 }
 
+// One tile of pass 2: start the next tile's loads into `nxt`, then the column partial sums of
+// this wave's 32 rows for the 128 keys in `cur` (written to red_w[0..127]).
+template <int D, int NT>
+__device__ __forceinline__ void colsum_tile(const __bf16* __restrict__ cur, __bf16* __restrict__ nxt,
+                                            bool prefetch, const TilePieces<D, NT>& tp, const __bf16* __restrict__ kg, int64_t kst,
+                                            int tile, int N, int tid, int ln, int half,
+                                            const bf16x8 (&qf)[D / 16], const float (&rc)[16], float c1,
+                                            float* __restrict__ red_w) {
+  if (prefetch) issue_tile_loads<D, NT>(tp, kg, kst, (tile + STAGES - 1) * KT, N, nxt, tid);
+  f32x16 acc = mma_subtile<D, false>(cur, 0, ln, half, qf);
+#pragma unroll
+  for (int sub = 0; sub < KT / 32; ++sub) {
+    f32x16 nxt_acc = acc;
+    if (sub + 1 < KT / 32) nxt_acc = mma_subtile<D, false>(cur, sub + 1, ln, half, qf);   // overlaps the exps below
+    float cs = 0.f;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) cs += fast_exp2(fmaf(acc[r], c1, -rc[r]));
+    const float other = __shfl_xor(cs, 32);
+    if (half == 0) red_w[sub * 32 + ln] = cs + other;
+    acc = nxt_acc;
+  }
+}
+
 // ---------------------------------------------------------------------------------------------
 // Pass 2: u_group[g][j] = sum over the M rows of 2^(c1*l_rj - rc_r),  j < T,
 // rc_r = rc_mul * row_const[g*M + r]  (log2-domain offset that already contains log2 Z_r).
@@ -186,16 +323,20 @@ score_colsum_kernel(const __bf16* __restrict__ q_obs, const __bf16* __restrict__
                     int64_t kst, int Hk, int M, int N, int T, int tiles_per_chunk, float c1,
                     const float* __restrict__ row_const, float rc_mul, float* __restrict__ u_group) {
   constexpr int NT = NW * 64;
-  constexpr int ROW = D + 8;
   constexpr int KS = D / 16;
-  __shared__ __attribute__((aligned(16))) __bf16 lds_k[KT * ROW];
-  __shared__ float red[NW][KT];
+  constexpr int TILE_ELEMS = KT * D;
+  __shared__ __attribute__((aligned(16))) __bf16 lds_k[STAGES * TILE_ELEMS];
+  __shared__ float red[2][NW][KT];              // per-wave column partials, double-buffered
 
   const int g = blockIdx.x % Hk, chunk = blockIdx.x / Hk;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, ln = lane & 31, half = lane >> 5;
   const int qrow = wave * 32 + ln;
-  ASL_LOAD_Q_FRAGS();
+  const __bf16* kg = k + (int64_t)g * ksh;
+  const int n_tiles_total = (T + KT - 1) / KT;
+  const int tile0 = chunk * tiles_per_chunk;
+  const int tile_end = min(tile0 + tiles_per_chunk, n_tiles_total);
 
+  ASL_LOAD_Q_FRAGS();
   float rc[16];
 #pragma unroll
   for (int r = 0; r < 16; ++r) {
@@ -203,46 +344,37 @@ score_colsum_kernel(const __bf16* __restrict__ q_obs, const __bf16* __restrict__
     const float v = row_const[(int64_t)g * M + min(row, M - 1)] * rc_mul;
     rc[r] = (row < M) ? v : INFINITY;                    // padded rows add 2^-inf = 0
   }
-
-  const __bf16* kg = k + (int64_t)g * ksh;
-  const int n_tiles_total = (T + KT - 1) / KT;
-  const int tile0 = chunk * tiles_per_chunk;
-  const int tile_end = min(tile0 + tiles_per_chunk, n_tiles_total);
-
-  ASL_KTILE_DECL(D, NT);
-  if (tile0 < tile_end) { ASL_KTILE_LOAD(tile0 * KT); }
-
-  for (int tile = tile0; tile < tile_end; ++tile) {
-    __syncthreads();                            // previous tile's LDS reads (keys and red) are done
-    ASL_KTILE_STORE();
-    __syncthreads();
-    if (tile + 1 < tile_end) { ASL_KTILE_LOAD((tile + 1) * KT); }
-
-    const int kbase = tile * KT;
+  TilePieces<D, NT> tp;
+  tp.init(kst, tid);
+  // prologue: STAGES-1 tiles in flight (after the loads above, so the in-order wait counts line up)
 #pragma unroll
-    for (int sub = 0; sub < KT / 32; ++sub) {
-      f32x16 acc;
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[r] = 0.f;
-      const __bf16* krow = lds_k + (sub * 32 + ln) * ROW + half * 8;
-#pragma unroll
-      for (int ks = 0; ks < KS; ++ks) {
-        bf16x8 kf = *reinterpret_cast<const bf16x8*>(krow + ks * 16);
-        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[ks], kf, acc, 0, 0, 0);   // [query row][key]
-      }
-      float cs = 0.f;
-#pragma unroll
-      for (int r = 0; r < 16; ++r) cs += fast_exp2(fmaf(acc[r], c1, -rc[r]));
-      const float other = __shfl_xor(cs, 32);
-      if (half == 0) red[wave][sub * 32 + ln] = cs + other;
-    }
-    __syncthreads();
+  for (int j = 0; j < STAGES - 1; ++j)
+    if (tile0 + j < tile_end) issue_tile_loads<D, NT>(tp, kg, kst, (tile0 + j) * KT, N, lds_k + j * TILE_ELEMS, tid);
+
+  // sum the waves' partials of one finished tile in a fixed order and store the past columns
+  auto reduce_store = [&](int buf_idx, int kbase) {
     for (int j = tid; j < KT; j += NT) {
-      float s = red[0][j];
+      float s = red[buf_idx][0][j];
 #pragma unroll
-      for (int w = 1; w < NW; ++w) s += red[w][j];
+      for (int w = 1; w < NW; ++w) s += red[buf_idx][w][j];
       if (kbase + j < T) u_group[(int64_t)g * T + kbase + j] = s;
     }
+  };
+
+  int stage = 0;                                  // buffer that holds tile `tile`
+  for (int tile = tile0; tile < tile_end; ++tile) {
+    const int it = tile - tile0;
+    wait_tile<D, NT>(tile + 1 < tile_end);
+    __syncthreads();      // tile `tile` has landed; previous tile's fragment reads and partials are done
+    if (it > 0) reduce_store((it - 1) & 1, (tile - 1) * KT);
+    const int free_stage = (stage == 0) ? STAGES - 1 : stage - 1;
+    colsum_tile<D, NT>(lds_k + stage * TILE_ELEMS, lds_k + free_stage * TILE_ELEMS, tile + STAGES - 1 < tile_end,
+                       tp, kg, kst, tile, N, tid, ln, half, qf, rc, c1, &red[it & 1][wave][0]);
+    stage = (stage + 1 == STAGES) ? 0 : stage + 1;
+  }
+  if (tile0 < tile_end) {
+    __syncthreads();
+    reduce_store((tile_end - 1 - tile0) & 1, (tile_end - 1) * KT);
   }
 }
 
@@ -319,10 +451,11 @@ bool score_mfma_supported(const asl_params& p) {
   return p.dtype == ASL_BF16 && (p.head_dim == 64 || p.head_dim == 128) && M <= 256;
 }
 
-// Key chunks per KV head: enough workgroups to fill 256 CUs a few times over.
+// Key chunks per KV head: one resident round of workgroups (256 CUs x 3 workgroups per CU with
+// 3 x 16 KB of LDS each), so that no second, partly filled round trails behind.
 int score_chunks(const asl_params& p) {
   const int n_tiles = (p.seq_len + KT - 1) / KT;
-  int want = (1024 + p.n_kv_heads - 1) / p.n_kv_heads;
+  int want = 768 / p.n_kv_heads;
   if (want > kMaxChunks) want = kMaxChunks;
   if (want > n_tiles) want = n_tiles;
   if (want < 1) want = 1;
