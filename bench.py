@@ -35,6 +35,7 @@ def main() -> int:
     ap.add_argument("--eager", action="store_true", help="time eager launches instead of HIP-graph replay")
     ap.add_argument("--copy-ref", action="store_true",
                     help="also run a plain 256 MiB device copy (a reference of known traffic for counter runs)")
+    ap.add_argument("--one-stream", action="store_true", help="no fork: rank/statistic and top-k/gather back to back")
     ap.add_argument("--breakdown", action="store_true", help="also time every kernel with events (untimed extra loop)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -56,6 +57,12 @@ def main() -> int:
     p = asl.make_params(sh.Hq, sh.Hk, sh.d, sh.N, sh.W, sh.S, sh.budget)
     up = lambda x: torch.from_numpy(x).to(dev).to(torch.bfloat16).contiguous()
     q, k, v = up(L.q_obs), up(L.k), up(L.v)
+    # Every layer of a real prefill has its own K/V, so consecutive steps must not find the previous
+    # step's K in the last-level cache: the steps cycle through N_SETS separately allocated K/V
+    # copies (each rolled along the token axis), about 0.5 GB per set at 128K.
+    N_SETS = 4
+    ks = [k] + [torch.roll(k, shifts=1000 * j, dims=1).contiguous() for j in range(1, N_SETS)]
+    vs = [v] + [torch.roll(v, shifts=1000 * j, dims=1).contiguous() for j in range(1, N_SETS)]
     T, n_idx = sh.T, sh.k + sh.W
     # P [Hk,T] and s [T] share one allocation so that one top-k call covers the Hk per-head rows
     # (Alg. 1) and the all-head row (Alg. 2) together
@@ -66,10 +73,13 @@ def main() -> int:
     I = torch.empty((sh.Hk + 1, n_idx), dtype=torch.int32, device=dev)   # rows 0..Hk-1 per head, row Hk all-head
     Kc = torch.empty((sh.Hk, n_idx, sh.d), dtype=torch.bfloat16, device=dev)
     Vc = torch.empty_like(Kc)
-    lse = None
+    lses = [None] * N_SETS
     if args.lse:
         from oracle import asl_oracle as orc          # input preparation for the one-pass mode only
-        lse = torch.from_numpy(orc.row_lse(L.q_obs, L.k, sh.W).astype(np.float32)).to(dev)
+        for j in range(N_SETS):
+            kj = ks[j].float().cpu().numpy()
+            lses[j] = torch.from_numpy(orc.row_lse(L.q_obs, kj, sh.W).astype(np.float32)).to(dev)
+    lse = lses[0]
 
     # Fill the rank ring with L_obs-1 earlier "layers" (perturbed scores) so that every timed step
     # evaluates the statistic over a full ring; tau = 0 never selects, so the ring stays full.
@@ -83,11 +93,29 @@ def main() -> int:
         layer += 1
     torch.cuda.synchronize()
 
+    # asl_rank_stat and asl_select_topk/asl_gather_kv both depend only on the scores and use disjoint
+    # parts of the workspace, so the step forks: ranking + statistic on the main stream, top-k +
+    # KV compaction on a side stream (both default priority), joined at the end of the step.
+    side = torch.cuda.Stream()
+    ev_scores, ev_side = torch.cuda.Event(), torch.cuda.Event()
+
     def step(layer_idx: int) -> None:
-        ctx.asl_score_layer(p, q, k, P, s, lse=lse)
+        kk, vv = ks[layer_idx % N_SETS], vs[layer_idx % N_SETS]
+        main = torch.cuda.current_stream()
+        ctx.asl_score_layer(p, q, kk, P, s, lse=lses[layer_idx % N_SETS])
+        if args.one_stream:
+            ctx.asl_rank_stat(p, s, layer_idx, 0, sh.L_obs, 0.0, ring, state, stat)
+            ctx.asl_select_topk(p, PS, sh.Hk + 1, I)
+            ctx.asl_gather_kv(p, kk, vv, I, sh.Hk, n_idx, Kc, Vc)
+            return
+        ev_scores.record(main)
+        with torch.cuda.stream(side):
+            side.wait_event(ev_scores)
+            ctx.asl_select_topk(p, PS, sh.Hk + 1, I)
+            ctx.asl_gather_kv(p, kk, vv, I, sh.Hk, n_idx, Kc, Vc)
+            ev_side.record(side)
         ctx.asl_rank_stat(p, s, layer_idx, 0, sh.L_obs, 0.0, ring, state, stat)
-        ctx.asl_select_topk(p, PS, sh.Hk + 1, I)
-        ctx.asl_gather_kv(p, k, v, I, sh.Hk, n_idx, Kc, Vc)
+        main.wait_event(ev_side)
 
     for _ in range(args.warmup):
         step(layer)
@@ -223,11 +251,12 @@ def main() -> int:
         "value": round(tokens_per_s, 1), "unit": "KV tokens/s per layer", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
-        "data": "synthetic (seeded numpy PCG64, bf16-rounded), resident in HBM",
+        "data": "synthetic (seeded numpy PCG64, bf16-rounded), resident in HBM; steps cycle through 4 K/V copies",
         "config": {"workload": workload[args.config], "seq_len": sh.N, "window": sh.W, "pool_kernel": sh.S,
                    "budget": sh.budget, "L_obs": sh.L_obs,
                    "score_mode": "lse supplied (one K pass)" if args.lse else "self-contained (two K passes)",
-                   "launch": "HIP graph replay (8 layers per graph)" if use_graph else "eager launches from Python",
+                   "launch": ("HIP graph replay (8 layers per graph)" if use_graph else "eager launches from Python")
+                             + ("" if args.one_stream else "; rank+statistic and top-k+gather on two streams"),
                    "eager_ms_per_step": round(eager_ms_per_step, 5),
                    "step": "score_layer + rank_stat(full ring) + select_topk(Hk per-head rows + the all-head row) + gather_kv(K,V per head)"},
         "roofline": roofline, "cpu_baseline": cpu,

@@ -11,8 +11,11 @@
  *    DEVICE pointers owned by the caller.  `params` and `ctx` are HOST pointers.  The library
  *    owns only the workspace inside asl_ctx (allocated by asl_create; no allocation afterwards).
  *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls enqueue work
- *    and return; they never synchronise.  One asl_ctx must be used by one stream at a time
- *    (calls sharing a ctx share its workspace and race if they overlap).
+ *    and return; they never synchronise.  Calls sharing a ctx share its workspace: calls of the
+ *    same family must not overlap.  The families use disjoint workspace regions, so one call each
+ *    of {asl_score_layer, asl_pool}, {asl_rank, asl_rankvar, asl_rank_stat}, {asl_select_topk} and
+ *    {asl_gather_kv} may run concurrently on different streams of the ctx's device (e.g. ranking
+ *    and top-k of the same scores side by side).
  *  - Return value: ASL_OK or a negative asl_status.  Arguments are validated on the host before
  *    any launch; asl_last_error() gives a message for the last failure on that ctx.
  *  - Notation: Hq query heads, Hk KV heads, G = Hq/Hk, d head dim, N sequence length,

@@ -86,12 +86,12 @@ sort_scatter_kernel(const float* __restrict__ s, const uint32_t* __restrict__ ke
   {
     const int me = blockIdx.x;
     int t = 0;
-    for (; t + 8 <= n_tiles; t += 8) {
-      uint32_t v[8];
+    for (; t + 16 <= n_tiles; t += 16) {
+      uint32_t v[16];
 #pragma unroll
-      for (int u = 0; u < 8; ++u) v[u] = tile_hist[(int64_t)(t + u) * 256 + tid];
+      for (int u = 0; u < 16; ++u) v[u] = tile_hist[(int64_t)(t + u) * 256 + tid];
 #pragma unroll
-      for (int u = 0; u < 8; ++u) {
+      for (int u = 0; u < 16; ++u) {
         tot += v[u];
         prev += (t + u < me) ? v[u] : 0u;
       }

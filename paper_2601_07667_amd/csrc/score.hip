@@ -13,6 +13,8 @@
 // them as the other MFMA operand (v_mfma_f32_32x32x16_bf16).  Pass 1 puts keys on the
 // accumulator's register axis (row statistics reduce in-lane), pass 2 puts query rows there
 // (column sums reduce in-lane).  All reductions have a fixed order: results are deterministic.
+#include <cstdlib>
+
 #include "asl_internal.h"
 
 namespace asl {
@@ -296,10 +298,10 @@ score_combine_kernel(const float* __restrict__ row_part, int Hk, int M, int n_ch
 template <int D, int NT>
 __device__ __forceinline__ void colsum_tile(const __bf16* __restrict__ cur, __bf16* __restrict__ nxt,
                                             bool prefetch, const TilePieces<D, NT>& tp, const __bf16* __restrict__ kg, int64_t kst,
-                                            int tile, int N, int tid, int ln, int half,
+                                            int prefetch_key0, int N, int tid, int ln, int half,
                                             const bf16x8 (&qf)[D / 16], const float (&rc)[16], float c1,
                                             float* __restrict__ red_w) {
-  if (prefetch) issue_tile_loads<D, NT>(tp, kg, kst, (tile + STAGES - 1) * KT, N, nxt, tid);
+  if (prefetch) issue_tile_loads<D, NT>(tp, kg, kst, prefetch_key0, N, nxt, tid);
   f32x16 acc = mma_subtile<D, false>(cur, 0, ln, half, qf);
 #pragma unroll
   for (int sub = 0; sub < KT / 32; ++sub) {
@@ -346,10 +348,13 @@ score_colsum_kernel(const __bf16* __restrict__ q_obs, const __bf16* __restrict__
   }
   TilePieces<D, NT> tp;
   tp.init(kst, tid);
+  // The chunk is walked from its last tile to its first: pass 1 walked it first to last, so the
+  // tiles read most recently (still in the last-level cache) are the ones this pass reads first.
+  const int n_my = max(tile_end - tile0, 0);
   // prologue: STAGES-1 tiles in flight (after the loads above, so the in-order wait counts line up)
 #pragma unroll
   for (int j = 0; j < STAGES - 1; ++j)
-    if (tile0 + j < tile_end) issue_tile_loads<D, NT>(tp, kg, kst, (tile0 + j) * KT, N, lds_k + j * TILE_ELEMS, tid);
+    if (j < n_my) issue_tile_loads<D, NT>(tp, kg, kst, (tile_end - 1 - j) * KT, N, lds_k + j * TILE_ELEMS, tid);
 
   // sum the waves' partials of one finished tile in a fixed order and store the past columns
   auto reduce_store = [&](int buf_idx, int kbase) {
@@ -361,20 +366,20 @@ score_colsum_kernel(const __bf16* __restrict__ q_obs, const __bf16* __restrict__
     }
   };
 
-  int stage = 0;                                  // buffer that holds tile `tile`
-  for (int tile = tile0; tile < tile_end; ++tile) {
-    const int it = tile - tile0;
-    wait_tile<D, NT>(tile + 1 < tile_end);
-    __syncthreads();      // tile `tile` has landed; previous tile's fragment reads and partials are done
-    if (it > 0) reduce_store((it - 1) & 1, (tile - 1) * KT);
+  int stage = 0;                                  // buffer that holds the current tile
+  for (int it = 0; it < n_my; ++it) {
+    const int tile = tile_end - 1 - it;
+    wait_tile<D, NT>(it + 1 < n_my);
+    __syncthreads();      // the tile has landed; previous tile's fragment reads and partials are done
+    if (it > 0) reduce_store((it - 1) & 1, (tile + 1) * KT);
     const int free_stage = (stage == 0) ? STAGES - 1 : stage - 1;
-    colsum_tile<D, NT>(lds_k + stage * TILE_ELEMS, lds_k + free_stage * TILE_ELEMS, tile + STAGES - 1 < tile_end,
-                       tp, kg, kst, tile, N, tid, ln, half, qf, rc, c1, &red[it & 1][wave][0]);
+    colsum_tile<D, NT>(lds_k + stage * TILE_ELEMS, lds_k + free_stage * TILE_ELEMS, it + STAGES - 1 < n_my,
+                       tp, kg, kst, (tile - (STAGES - 1)) * KT, N, tid, ln, half, qf, rc, c1, &red[it & 1][wave][0]);
     stage = (stage + 1 == STAGES) ? 0 : stage + 1;
   }
-  if (tile0 < tile_end) {
+  if (n_my > 0) {
     __syncthreads();
-    reduce_store((tile_end - 1 - tile0) & 1, (tile_end - 1) * KT);
+    reduce_store((n_my - 1) & 1, tile0 * KT);
   }
 }
 
@@ -451,11 +456,16 @@ bool score_mfma_supported(const asl_params& p) {
   return p.dtype == ASL_BF16 && (p.head_dim == 64 || p.head_dim == 128) && M <= 256;
 }
 
-// Key chunks per KV head: one resident round of workgroups (256 CUs x 3 workgroups per CU with
-// 3 x 16 KB of LDS each), so that no second, partly filled round trails behind.
+// Key chunks per KV head: one resident round of workgroups, so that no second, partly filled
+// round trails behind.  Tunable through ASL_SCORE_WORKGROUPS (total workgroups per pass).
 int score_chunks(const asl_params& p) {
+  static const int target = [] {
+    const char* e = getenv("ASL_SCORE_WORKGROUPS");
+    const int v = e ? atoi(e) : 0;
+    return v > 0 ? v : 768;
+  }();
   const int n_tiles = (p.seq_len + KT - 1) / KT;
-  int want = 768 / p.n_kv_heads;
+  int want = target / p.n_kv_heads;
   if (want > kMaxChunks) want = kMaxChunks;
   if (want > n_tiles) want = n_tiles;
   if (want < 1) want = 1;

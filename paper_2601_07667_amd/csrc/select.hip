@@ -47,12 +47,12 @@ __device__ __forceinline__ Pick pick_digit(const uint32_t* __restrict__ hp, int 
   uint32_t tot = 0, prev = 0;
   const uint32_t mine = hp[(int64_t)me * 256 + tid];
   int t = 0;
-  for (; t + 8 <= n_tiles; t += 8) {
-    uint32_t v[8];
+  for (; t + 16 <= n_tiles; t += 16) {
+    uint32_t v[16];
 #pragma unroll
-    for (int u = 0; u < 8; ++u) v[u] = hp[(int64_t)(t + u) * 256 + tid];
+    for (int u = 0; u < 16; ++u) v[u] = hp[(int64_t)(t + u) * 256 + tid];
 #pragma unroll
-    for (int u = 0; u < 8; ++u) {
+    for (int u = 0; u < 16; ++u) {
       tot += v[u];
       prev += (t + u < me) ? v[u] : 0u;
     }
