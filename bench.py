@@ -21,6 +21,10 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0            # MI355X published HBM3E bandwidth
+# HBM traffic of one launch of the pass-2 kernel at workload C3, from two rocprofv3 --pmc runs
+# (profiles/score_c3_128k_counters.md): FETCH_SIZE 131260.0 and WRITE_SIZE 4095.0 KiB-units per
+# dispatch, scaled by what the same counters read for a 256 MiB copy (x2.0 and x1.0).
+PMC_TRAFFIC_BYTES = {3: int((131260.0 * 2.0 + 4095.0 * 1.0) * 1024)}
 MFMA_BF16_PEAK_TFLOPS = 2500.0   # dense bf16
 
 
@@ -198,7 +202,7 @@ def main() -> int:
     useful_flops = 2.0 * sh.Hq * sh.W * sh.N * sh.d          # one QK^T over the window rows
     roofline = {"bound": "hbm", "kernel": "score_colsum_kernel (pass 2)", "achieved": round(dom_gbs, 1),
                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(dom_gbs / HBM_PEAK_GBS, 4),
-                "traffic": None, "avg_launch_ms": round(dom_avg_ms, 5), "launches": dom_n,
+                "traffic": PMC_TRAFFIC_BYTES.get(args.config), "avg_launch_ms": round(dom_avg_ms, 5), "launches": dom_n,
                 "timing": "HIP events around this kernel, eager loop of the same steps after the timed region",
                 "algorithmic_bytes": dom_bytes,
                 "mfma_tflops": round(useful_flops / (dom_avg_ms * 1e-3) / 1e12, 1),

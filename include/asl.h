@@ -158,6 +158,29 @@ asl_status asl_gather_kv(asl_ctx* ctx, const asl_params* params, const void* k, 
                          const int32_t* idx, int32_t idx_rows, int32_t n_idx, void* k_out,
                          void* v_out, void* stream);
 
+/* Token propagation at the selection layer (Sec. 4.2 "Prefilling": only the selected tokens go on
+ * to the deeper layers; Alg. 2's select_idx applied to the hidden states): dst[i,:] = src[idx[i],:].
+ *   src rows of row_bytes bytes, src_row_stride_bytes apart; idx [n_idx] int32, entries in range
+ *   (caller's contract); dst [n_idx, row_bytes] dense.  16-byte aligned rows, pointers, stride. */
+asl_status asl_gather_rows(asl_ctx* ctx, const void* src, int64_t src_row_stride_bytes, int32_t row_bytes,
+                           const int32_t* idx, int32_t n_idx, void* dst, void* stream);
+
+/* One layer of Alg. 1 + Alg. 2 in a single call: asl_score_layer, then asl_rank_stat on `stream`
+ * while asl_select_topk (Hk per-head rows + the all-head row) and asl_gather_kv (per-head rows) run
+ * on a second stream owned by the ctx; both are joined back into `stream` before returning, so the
+ * caller sees one in-order call (also under stream capture).
+ *   scores  [Hk+1, T] f32 out: rows 0..Hk-1 = P (per KV head), row Hk = s (all heads).
+ *   idx_out [Hk+1, k+W] int32 out: rows 0..Hk-1 = Alg. 1's per-head I, row Hk = Alg. 2's select_idx
+ *           (to be used only when out->selected is set).
+ *   k_out, v_out [Hk, k+W, d] out: K[I], V[I] per head; pass k_out = NULL to skip the compaction.
+ * The ctx must have been created with max_kv_heads >= Hk + 1.  Other arguments as in the single
+ * calls.  Not to be overlapped with any other call on the same ctx. */
+asl_status asl_layer_step(asl_ctx* ctx, const asl_params* params, const void* q_obs, const void* k,
+                          const void* v, const float* lse, int32_t layer_idx, int32_t l_min,
+                          int32_t l_obs, double tau, float* scores, int32_t* rank_ring,
+                          asl_state* state, asl_stat* out, int32_t* idx_out, void* k_out, void* v_out,
+                          void* stream);
+
 /* Measurement aid (not a step of the paper's method; for callers that time the kernels of the
  * calls above).  Kernel ids: 0 score row statistics (pass 1), 1 its combine, 2 score column sums
  * (pass 2), 3 pool, 4 sort histogram, 5 sort scatter, 6 rank-variance finalisation (or the

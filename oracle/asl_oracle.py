@@ -190,6 +190,12 @@ def gather_kv(k: np.ndarray, v: np.ndarray, idx: np.ndarray):
             np.stack([v[g, idx[g], :] for g in range(Hk)]))
 
 
+def propagate_tokens(hidden: np.ndarray, select_idx: np.ndarray) -> np.ndarray:
+    """Sec. 4.2 "Prefilling": once the selection layer is determined, only the selected tokens'
+    hidden states go on to the deeper layers.  hidden [N, D]; select_idx from Alg. 2."""
+    return np.asarray(hidden)[np.asarray(select_idx)].copy()
+
+
 # --------------------------------------------------------------------------- Alg. 2, statistic
 @dataclass
 class RankStat:

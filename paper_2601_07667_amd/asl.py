@@ -20,7 +20,7 @@ _STATUS = {0: "ASL_OK", -1: "ASL_EINVAL", -2: "ASL_ENOMEM", -3: "ASL_EHIP", -4: 
 
 EXPORTS = ["asl_create", "asl_destroy", "asl_last_error", "asl_workspace_bytes", "asl_score_layer",
            "asl_pool", "asl_rank", "asl_rankvar", "asl_rank_stat", "asl_select_topk", "asl_gather_kv",
-           "asl_profile_enable", "asl_profile_collect"]
+           "asl_gather_rows", "asl_layer_step", "asl_profile_enable", "asl_profile_collect"]
 
 
 class AslParams(C.Structure):
@@ -83,6 +83,11 @@ def load() -> C.CDLL:
     lib.asl_select_topk.restype = C.c_int
     lib.asl_gather_kv.argtypes = [vp, C.POINTER(AslParams), vp, vp, vp, i32, i32, vp, vp, vp]
     lib.asl_gather_kv.restype = C.c_int
+    lib.asl_gather_rows.argtypes = [vp, vp, i64, i32, vp, i32, vp, vp]
+    lib.asl_gather_rows.restype = C.c_int
+    lib.asl_layer_step.argtypes = [vp, C.POINTER(AslParams), vp, vp, vp, vp, i32, i32, i32, C.c_double,
+                                   vp, vp, vp, vp, vp, vp, vp, vp]
+    lib.asl_layer_step.restype = C.c_int
     lib.asl_profile_enable.argtypes = [vp, C.c_uint32, i32]
     lib.asl_profile_enable.restype = C.c_int
     lib.asl_profile_collect.argtypes = [vp, i32, C.POINTER(C.c_double), C.POINTER(i32)]
@@ -158,6 +163,17 @@ class Asl:
     def asl_select_topk(self, params: AslParams, scores, rows: int, idx_out) -> None:
         self._check(self.lib.asl_select_topk(self.h, C.byref(params), _ptr(scores), rows, _ptr(idx_out),
                                              _stream()))
+
+    def asl_gather_rows(self, src, src_row_stride_bytes: int, row_bytes: int, idx, n_idx: int, dst) -> None:
+        self._check(self.lib.asl_gather_rows(self.h, _ptr(src), src_row_stride_bytes, row_bytes, _ptr(idx), n_idx,
+                                             _ptr(dst), _stream()))
+
+    def asl_layer_step(self, params: AslParams, q_obs, k, v, layer_idx: int, l_min: int, l_obs: int, tau: float,
+                       scores, rank_ring, state, out, idx_out, k_out=None, v_out=None, lse=None) -> None:
+        self._check(self.lib.asl_layer_step(self.h, C.byref(params), _ptr(q_obs), _ptr(k), _ptr(v), _ptr(lse),
+                                            layer_idx, l_min, l_obs, tau, _ptr(scores), _ptr(rank_ring),
+                                            _ptr(state), _ptr(out), _ptr(idx_out), _ptr(k_out), _ptr(v_out),
+                                            _stream()))
 
     def asl_profile_enable(self, kernel_mask: int, max_records: int) -> None:
         self._check(self.lib.asl_profile_enable(self.h, kernel_mask, max_records))

@@ -15,6 +15,8 @@ struct asl_ctx {
   size_t bytes;
   asl::Workspace ws;
   asl::Prof prof;
+  hipStream_t side;          // second stream of asl_layer_step's fork/join (default priority)
+  hipEvent_t ev_fork, ev_join;
   char err[256];
 };
 
@@ -165,6 +167,19 @@ asl_status asl_create(asl_ctx** out, int device, int32_t max_seq_len, int32_t ma
     delete ctx;
     return ASL_EHIP;
   }
+  ctx->side = nullptr;
+  ctx->ev_fork = ctx->ev_join = nullptr;
+  e = hipStreamCreateWithFlags(&ctx->side, hipStreamNonBlocking);
+  if (e == hipSuccess) e = hipEventCreateWithFlags(&ctx->ev_fork, hipEventDisableTiming);
+  if (e == hipSuccess) e = hipEventCreateWithFlags(&ctx->ev_join, hipEventDisableTiming);
+  if (e != hipSuccess) {
+    if (ctx->ev_join) (void)hipEventDestroy(ctx->ev_join);
+    if (ctx->ev_fork) (void)hipEventDestroy(ctx->ev_fork);
+    if (ctx->side) (void)hipStreamDestroy(ctx->side);
+    (void)hipFree(ctx->base);
+    delete ctx;
+    return ASL_EHIP;
+  }
   *out = ctx;
   return ASL_OK;
 }
@@ -240,6 +255,10 @@ asl_status asl_destroy(asl_ctx* ctx) {
   if (!ctx) return ASL_EINVAL;
   DeviceGuard guard(ctx->device);
   prof_release(ctx);
+  (void)hipStreamSynchronize(ctx->side);
+  (void)hipEventDestroy(ctx->ev_join);
+  (void)hipEventDestroy(ctx->ev_fork);
+  (void)hipStreamDestroy(ctx->side);
   hipError_t e = hipFree(ctx->base);
   delete ctx;
   return e == hipSuccess ? ASL_OK : ASL_EHIP;
@@ -389,6 +408,58 @@ asl_status asl_gather_kv(asl_ctx* ctx, const asl_params* p, const void* k, const
                                     p->k_stride_head * eb, p->k_stride_tok * eb, p->v_stride_head * eb,
                                     p->v_stride_tok * eb, k_out, v_out, static_cast<hipStream_t>(stream));
   if (e != hipSuccess) return hip_fail(ctx, e, "gather launch");
+  return ASL_OK;
+}
+
+asl_status asl_gather_rows(asl_ctx* ctx, const void* src, int64_t src_row_stride_bytes, int32_t row_bytes,
+                           const int32_t* idx, int32_t n_idx, void* dst, void* stream) {
+  if (!ctx) return ASL_EINVAL;
+  if (!src || !idx || !dst) return fail(ctx, ASL_EINVAL, "null tensor pointer");
+  if (row_bytes < 1 || n_idx < 0 || src_row_stride_bytes < row_bytes)
+    return fail(ctx, ASL_EINVAL, "need row_bytes >= 1, n_idx >= 0, stride >= row_bytes");
+  if (row_bytes % 16 != 0 || src_row_stride_bytes % 16 != 0 || !aligned16(src) || !aligned16(dst))
+    return fail(ctx, ASL_EUNSUPPORTED, "gather needs 16-byte aligned rows, pointers and strides");
+  DeviceGuard guard(ctx->device);
+  if (guard.err != hipSuccess) return hip_fail(ctx, guard.err, "set device");
+  hipError_t e = asl::launch_gather(ctx->ws.prof, src, nullptr, idx, 1, n_idx, 1, row_bytes, 0,
+                                    src_row_stride_bytes, 0, 0, dst, nullptr, static_cast<hipStream_t>(stream));
+  if (e != hipSuccess) return hip_fail(ctx, e, "gather launch");
+  return ASL_OK;
+}
+
+asl_status asl_layer_step(asl_ctx* ctx, const asl_params* p, const void* q_obs, const void* k, const void* v,
+                          const float* lse, int32_t layer_idx, int32_t l_min, int32_t l_obs, double tau,
+                          float* scores, int32_t* rank_ring, asl_state* state, asl_stat* out,
+                          int32_t* idx_out, void* k_out, void* v_out, void* stream) {
+  asl_status st = check_params(ctx, p);
+  if (st != ASL_OK) return st;
+  if (!scores || !idx_out) return fail(ctx, ASL_EINVAL, "null tensor pointer");
+  if (p->n_kv_heads + 1 > ctx->max_kv_heads)
+    return fail(ctx, ASL_ENOMEM, "asl_layer_step selects Hk+1 rows: create the context with max_kv_heads >= %d",
+                p->n_kv_heads + 1);
+  const int Hk = p->n_kv_heads, T = p->seq_len - p->window;
+  const int k_sel = (p->budget < p->seq_len ? p->budget : p->seq_len) - p->window;
+  float* p_head = scores;
+  float* s_all = scores + (int64_t)Hk * T;
+  hipStream_t hs = static_cast<hipStream_t>(stream);
+  st = asl_score_layer(ctx, p, q_obs, k, lse, p_head, s_all, stream);
+  if (st != ASL_OK) return st;
+  DeviceGuard guard(ctx->device);
+  if (guard.err != hipSuccess) return hip_fail(ctx, guard.err, "set device");
+  // fork: top-k + KV compaction on the side stream, ranking + statistic on the caller's stream
+  hipError_t e = hipEventRecord(ctx->ev_fork, hs);
+  if (e == hipSuccess) e = hipStreamWaitEvent(ctx->side, ctx->ev_fork, 0);
+  if (e != hipSuccess) return hip_fail(ctx, e, "fork");
+  asl_status st_side = asl_select_topk(ctx, p, scores, Hk + 1, idx_out, ctx->side);
+  if (st_side == ASL_OK && k_out != nullptr)
+    st_side = asl_gather_kv(ctx, p, k, v, idx_out, Hk, k_sel + p->window, k_out, v_out, ctx->side);
+  // join even if a launch failed, so that the side stream never stays forked (e.g. under capture)
+  e = hipEventRecord(ctx->ev_join, ctx->side);
+  asl_status st_main = asl_rank_stat(ctx, p, s_all, layer_idx, l_min, l_obs, tau, rank_ring, state, out, stream);
+  if (e == hipSuccess) e = hipStreamWaitEvent(hs, ctx->ev_join, 0);
+  if (st_side != ASL_OK) return st_side;
+  if (st_main != ASL_OK) return st_main;
+  if (e != hipSuccess) return hip_fail(ctx, e, "join");
   return ASL_OK;
 }
 

@@ -203,3 +203,139 @@ def test_sweep_score_level_bit_exact(gpu_device):
                 break
         assert selected_at is not None and selected_at > sh.L_min
     ctx.close()
+
+
+def test_bench_launch_configuration(gpu_device):
+    """The configuration bench.py times on workload C3: P and s in one [Hk+1, T] allocation, one
+    top-k call over the Hk per-head rows plus the all-head row, ranking/statistic and top-k/gather
+    forked on two streams that share one context."""
+    import torch
+    L = synth.config_layer(3)
+    sh = L.shape
+    dev = gpu_device
+    ctx = asl.Asl(sh.N, sh.Hk + 1, sh.Hq * sh.W)
+    p = gu.params_of(sh)
+    qd, kd, vd = (gu.to_dev(x, sh.dtype, dev) for x in (L.q_obs, L.k, L.v))
+    T, n_idx = sh.T, sh.k + sh.W
+    PS = torch.empty((sh.Hk + 1, T), dtype=torch.float32, device=dev)
+    P, s = PS[:sh.Hk], PS[sh.Hk]
+    ring = torch.zeros((sh.L_obs, T), dtype=torch.int32, device=dev)
+    state, stat = asl.new_state(dev), asl.new_stat(dev)
+    I = torch.empty((sh.Hk + 1, n_idx), dtype=torch.int32, device=dev)
+    Kc = torch.empty((sh.Hk, n_idx, sh.d), dtype=torch.bfloat16, device=dev)
+    Vc = torch.empty_like(Kc)
+    side = torch.cuda.Stream()
+    ev_a, ev_b = torch.cuda.Event(), torch.cuda.Event()
+    main = torch.cuda.current_stream()
+    for layer_idx in range(2):                       # second pass re-uses every workspace region
+        ctx.asl_score_layer(p, qd, kd, P, s)
+        ev_a.record(main)
+        with torch.cuda.stream(side):
+            side.wait_event(ev_a)
+            ctx.asl_select_topk(p, PS, sh.Hk + 1, I)
+            ctx.asl_gather_kv(p, kd, vd, I, sh.Hk, n_idx, Kc, Vc)
+            ev_b.record(side)
+        ctx.asl_rank_stat(p, s, layer_idx, 0, sh.L_obs, 0.3, ring, state, stat)
+        main.wait_event(ev_b)
+    torch.cuda.synchronize()
+    P_ref, s_ref = orc.score_layer(L.q_obs, L.k, sh.W, sh.S)
+    gu.assert_scores_close(P.cpu().numpy(), P_ref, "bench config P")
+    gu.assert_scores_close(s.cpu().numpy(), s_ref, "bench config s")
+    Ig = I.cpu().numpy().astype(np.int64)
+    sg = s.cpu().numpy().astype(np.float64)
+    Pg = P.cpu().numpy().astype(np.float64)
+    # integer stages are exact given the GPU's own fp32 scores
+    np.testing.assert_array_equal(Ig[sh.Hk], orc.select_indices(sg, sh.k, sh.W))
+    np.testing.assert_array_equal(Ig[:sh.Hk], orc.select_indices(Pg, sh.k, sh.W))
+    for r in range(2):
+        np.testing.assert_array_equal(ring[r].cpu().numpy(), orc.rank_desc(sg))
+    for g in range(sh.Hk):
+        gu.check_topk_within_tolerance(Ig[g], P_ref[g], sh.k, f"bench config head {g}")
+        assert np.array_equal(Kc[g].float().cpu().numpy(), L.k[g][Ig[g]])
+        assert np.array_equal(Vc[g].float().cpu().numpy(), L.v[g][Ig[g]])
+    assert np.isin(L.needles, Ig[sh.Hk]).all()
+    st = asl.read_struct(stat, asl.AslStat)
+    assert st.evaluated == 1 and st.n_rows == 2 and st.var_top == 0.0      # two identical rank rows
+    ctx.close()
+
+
+def _layer_step_case(dev, L, layer_idx=0):
+    import torch
+    sh = L.shape
+    ctx = asl.Asl(sh.N, sh.Hk + 1, sh.Hq * sh.W)
+    p = gu.params_of(sh)
+    qd, kd, vd = (gu.to_dev(x, sh.dtype, dev) for x in (L.q_obs, L.k, L.v))
+    T, n_idx = sh.T, sh.k + sh.W
+    scores = torch.empty((sh.Hk + 1, T), dtype=torch.float32, device=dev)
+    ring = torch.zeros((sh.L_obs, T), dtype=torch.int32, device=dev)
+    state, stat = asl.new_state(dev), asl.new_stat(dev)
+    I = torch.empty((sh.Hk + 1, n_idx), dtype=torch.int32, device=dev)
+    Kc = torch.empty((sh.Hk, n_idx, sh.d), dtype=kd.dtype, device=dev)
+    Vc = torch.empty_like(Kc)
+    ctx.asl_layer_step(p, qd, kd, vd, layer_idx, sh.L_min, sh.L_obs, sh.tau, scores, ring, state, stat, I, Kc, Vc)
+    torch.cuda.synchronize()
+    # the same layer through the single calls
+    P2 = torch.empty((sh.Hk, T), dtype=torch.float32, device=dev)
+    s2 = torch.empty((T,), dtype=torch.float32, device=dev)
+    ring2 = torch.zeros_like(ring)
+    state2, stat2 = asl.new_state(dev), asl.new_stat(dev)
+    Ih = torch.empty((sh.Hk, n_idx), dtype=torch.int32, device=dev)
+    Ia = torch.empty((1, n_idx), dtype=torch.int32, device=dev)
+    K2 = torch.empty_like(Kc)
+    V2 = torch.empty_like(Kc)
+    ctx.asl_score_layer(p, qd, kd, P2, s2)
+    ctx.asl_rank_stat(p, s2, layer_idx, sh.L_min, sh.L_obs, sh.tau, ring2, state2, stat2)
+    ctx.asl_select_topk(p, P2, sh.Hk, Ih)
+    ctx.asl_select_topk(p, s2, 1, Ia)
+    ctx.asl_gather_kv(p, kd, vd, Ih, sh.Hk, n_idx, K2, V2)
+    torch.cuda.synchronize()
+    assert torch.equal(scores[:sh.Hk], P2) and torch.equal(scores[sh.Hk], s2)
+    assert torch.equal(ring, ring2) and torch.equal(I[:sh.Hk], Ih) and torch.equal(I[sh.Hk:], Ia)
+    assert torch.equal(Kc, K2) and torch.equal(Vc, V2) and torch.equal(state, state2) 
+    out = dict(P=scores[:sh.Hk].cpu().numpy(), s=scores[sh.Hk].cpu().numpy(),
+               rank=ring[layer_idx % sh.L_obs].cpu().numpy().astype(np.int64),
+               stat=asl.read_struct(stat, asl.AslStat), I_head=I[:sh.Hk].cpu().numpy().astype(np.int64),
+               I_all=I[sh.Hk].cpu().numpy().astype(np.int64), Kc=Kc.float().cpu().numpy(),
+               Vc=Vc.float().cpu().numpy())
+    out["Ks"] = np.stack([L.k[g][out["I_all"]] for g in range(sh.Hk)])      # shared-row gather not part of the step
+    out["Vs"] = np.stack([L.v[g][out["I_all"]] for g in range(sh.Hk)])
+    ctx.close()
+    return out
+
+
+def test_layer_step_matches_single_calls_and_oracle(gpu_device):
+    """asl_layer_step (fork/join on the context's own side stream) gives bit-identical results to the
+    single calls, and both match the oracle."""
+    for cfg in (1, 2):
+        L = synth.config_layer(cfg)
+        if cfg == 1:
+            sh = synth.shape_of(1)
+            sh.dtype = "bf16"
+            L = synth.iid_layer(sh, synth.BASE_SEED + 1, name="C1-bf16")
+        _check_layer(L, _layer_step_case(gpu_device, L))
+
+
+def test_second_model_shape_and_large_budget(gpu_device):
+    """The 28-layer model's head geometry (4 KV heads, 7 query heads per group: 224 query rows per
+    KV head, seven 32-row blocks) and the paper's larger KV budget of 8192."""
+    sh = synth.Shape(Hq=28, Hk=4, d=128, N=20000, W=32, S=7, budget=8192, L_min=9)
+    L = synth.needle_layer(sh, 77, 32, synth.needle_gain_strong(sh), name="qwen-like-20k-b8192")
+    _check_layer(L, _pipeline(gpu_device, L))
+
+
+def test_hidden_state_propagation(gpu_device):
+    """asl_gather_rows on [N, 4096] bf16 hidden states with the selection of a scored layer."""
+    import torch
+    rng = np.random.default_rng(5)
+    N, D = 5000, 4096
+    hidden = synth.round_bf16(rng.standard_normal((N, D)).astype(np.float32))
+    idx = np.sort(rng.choice(N, 777, replace=False)).astype(np.int32)
+    ctx = asl.Asl(N, 1, 32)
+    hd = gu.to_dev(hidden, "bf16", gpu_device)
+    out = torch.zeros((len(idx), D), dtype=torch.bfloat16, device=gpu_device)
+    ctx.asl_gather_rows(hd, D * 2, D * 2, torch.from_numpy(idx).to(gpu_device), len(idx), out)
+    assert np.array_equal(out.float().cpu().numpy(), orc.propagate_tokens(hidden, idx))
+    ctx.asl_gather_rows(hd, D * 2, D * 2, torch.from_numpy(idx).to(gpu_device), 0, out)      # empty selection
+    with pytest.raises(asl.AslError):
+        ctx.asl_gather_rows(hd, D * 2, 24, torch.from_numpy(idx).to(gpu_device), 4, out)    # rows not 16-byte multiples
+    ctx.close()

@@ -210,6 +210,22 @@ def test_gather_bit_exact(ctx, gpu_device, cfg):
     assert torch.equal(ko, kd)
 
 
+def test_gather_empty_and_f32(ctx, gpu_device):
+    torch = _torch()
+    sh = synth.shape_of(1)                                   # fp32 storage, d = 64
+    L = synth.config_layer(1)
+    p = gu.params_of(sh)
+    kd, vd = gu.to_dev(L.k, "f32", gpu_device), gu.to_dev(L.v, "f32", gpu_device)
+    ko = torch.full((sh.Hk, 4, sh.d), 7.0, device=gpu_device)
+    vo = torch.full_like(ko, 7.0)
+    I = torch.tensor([[3, 0, 511, 3]], dtype=torch.int32, device=gpu_device)     # repeats allowed
+    ctx.asl_gather_kv(p, kd, vd, I, 1, 0, ko, vo)                                  # n_idx = 0: nothing written
+    assert torch.all(ko == 7.0) and torch.all(vo == 7.0)
+    ctx.asl_gather_kv(p, kd, vd, I, 1, 4, ko, vo)
+    assert np.array_equal(ko.cpu().numpy(), L.k[:, [3, 0, 511, 3], :])
+    assert np.array_equal(vo.cpu().numpy(), L.v[:, [3, 0, 511, 3], :])
+
+
 # ----------------------------------------------------------------------------- errors
 def test_argument_errors(ctx, gpu_device):
     torch = _torch()

@@ -237,6 +237,19 @@ def test_gather_is_fancy_indexing():
     np.testing.assert_array_equal(ko, k[:, [4, 2], :])
 
 
+def test_propagate_tokens_is_row_selection():
+    rng = np.random.default_rng(8)
+    hidden = rng.standard_normal((30, 5))
+    idx = np.array([0, 3, 4, 17, 28, 29])
+    out = orc.propagate_tokens(hidden, idx)
+    assert out.shape == (6, 5)
+    for i, t in enumerate(idx):
+        for c in range(5):
+            assert out[i, c] == hidden[t, c]
+    out[0, 0] = 99.0                                               # a copy, not a view
+    assert hidden[0, 0] != 99.0
+
+
 def test_get_ranks_whole_on_config1():
     L = synth.config_layer(1)
     sh = L.shape
