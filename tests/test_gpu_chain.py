@@ -339,3 +339,84 @@ def test_hidden_state_propagation(gpu_device):
     with pytest.raises(asl.AslError):
         ctx.asl_gather_rows(hd, D * 2, 24, torch.from_numpy(idx).to(gpu_device), 4, out)    # rows not 16-byte multiples
     ctx.close()
+
+
+def test_ring_restart_and_cyclic_continuity(gpu_device):
+    """A layer index whose ring row does not follow the previous one restarts the rank cache; indices
+    that wrap round the ring (as in a replayed graph of L_obs layers) keep it."""
+    import torch
+    sh = synth.shape_of(1)
+    ctx = gu.ctx_for(sh)
+    p = gu.params_of(sh)
+    T, L_obs = sh.T, 4
+    rng = np.random.default_rng(0)
+    ring = torch.zeros((L_obs, T), dtype=torch.int32, device=gpu_device)
+    state, stat = asl.new_state(gpu_device), asl.new_stat(gpu_device)
+    def push(layer):
+        s = torch.from_numpy(rng.random(T, dtype=np.float32)).to(gpu_device)
+        ctx.asl_rank_stat(p, s, layer, 0, L_obs, 0.0, ring, state, stat)
+        return asl.read_struct(state, asl.AslState), asl.read_struct(stat, asl.AslStat)
+    assert push(0)[0].n_valid_rows == 1
+    assert push(1)[0].n_valid_rows == 2
+    st, out = push(2)
+    assert st.n_valid_rows == 3 and out.evaluated == 1 and out.n_rows == 3
+    assert push(3)[0].n_valid_rows == 4
+    assert push(0)[0].n_valid_rows == 4            # wraps round the ring: still consecutive rows
+    assert push(5)[0].n_valid_rows == 4            # 5 % 4 == 1 follows 0
+    st, out = push(7)                              # 7 % 4 == 3 does not follow 1: restart
+    assert st.n_valid_rows == 1 and st.last_layer == 7 and out.evaluated == 0
+    ctx.close()
+
+
+def test_layer_step_graph_replay_matches_eager(gpu_device):
+    """Capture L_obs consecutive asl_layer_step calls in a HIP graph, replay it several times with
+    eager work and synchronisations in between, and compare every replay with the eager result."""
+    import torch
+    sh = synth.Shape(Hq=8, Hk=2, d=128, N=6000, W=32, S=7, budget=256, L_obs=4, L_min=0)
+    layers = [synth.iid_layer(sh, 100 + j) for j in range(sh.L_obs)]
+    dev = gpu_device
+    ctx = asl.Asl(sh.N, sh.Hk + 1, sh.Hq * sh.W)
+    p = gu.params_of(sh)
+    T, n_idx = sh.T, sh.k + sh.W
+    qs = [gu.to_dev(L.q_obs, "bf16", dev) for L in layers]
+    kss = [gu.to_dev(L.k, "bf16", dev) for L in layers]
+    vss = [gu.to_dev(L.v, "bf16", dev) for L in layers]
+
+    def buffers():
+        return dict(scores=torch.zeros((sh.L_obs, sh.Hk + 1, T), dtype=torch.float32, device=dev),
+                    ring=torch.zeros((sh.L_obs, T), dtype=torch.int32, device=dev),
+                    state=asl.new_state(dev), stats=torch.zeros((sh.L_obs, 40), dtype=torch.uint8, device=dev),
+                    I=torch.zeros((sh.L_obs, sh.Hk + 1, n_idx), dtype=torch.int32, device=dev),
+                    K=torch.zeros((sh.L_obs, sh.Hk, n_idx, sh.d), dtype=torch.bfloat16, device=dev),
+                    V=torch.zeros((sh.L_obs, sh.Hk, n_idx, sh.d), dtype=torch.bfloat16, device=dev))
+
+    def trip(b, first_layer):
+        for j in range(sh.L_obs):
+            ctx.asl_layer_step(p, qs[j], kss[j], vss[j], first_layer + j, 0, sh.L_obs, 0.0, b["scores"][j], b["ring"],
+                               b["state"], b["stats"][j], b["I"][j], b["K"][j], b["V"][j])
+
+    ref = buffers()
+    trip(ref, 0)
+    trip(ref, sh.L_obs)                              # second trip: the ring is full, statistic over 4 rows
+    torch.cuda.synchronize()
+    g = buffers()
+    trip(g, 0)                                       # warm the ring eagerly, then capture the second trip
+    torch.cuda.synchronize()
+    cap = torch.cuda.Stream()
+    cap.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(cap):
+        with torch.cuda.graph(graph, stream=cap):
+            trip(g, sh.L_obs)
+    torch.cuda.synchronize()
+    for rep in range(3):
+        for t in (g["scores"], g["I"], g["K"], g["V"], g["stats"]):
+            t.zero_()                                # eager work between replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for name in ("scores", "ring", "I", "K", "V", "stats"):
+            assert torch.equal(g[name], ref[name]), f"replay {rep}: {name} differs from the eager result"
+    st = asl.read_struct(g["stats"][sh.L_obs - 1], asl.AslStat)
+    assert st.evaluated == 1 and st.n_rows == sh.L_obs
+    ctx.close()
