@@ -41,6 +41,7 @@ def main() -> int:
     ap.add_argument("--copy-ref", action="store_true",
                     help="also run a plain 256 MiB device copy (a reference of known traffic for counter runs)")
     ap.add_argument("--one-stream", action="store_true", help="no fork: rank/statistic and top-k/gather back to back")
+    ap.add_argument("--no-batched-gather", action="store_true", help="skip the 32-layer batched KV-compaction leg")
     ap.add_argument("--breakdown", action="store_true", help="also time every kernel with events (untimed extra loop)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -238,6 +239,39 @@ def main() -> int:
                 kernels[name] = {"us_per_step": round(ms * 1e3 / n_b, 2), "launches_per_step": n / n_b}
         ctx.asl_profile_enable(0, 0)
 
+    # Bandwidth of the KV compaction where bandwidth, not launch latency, is the limit: one
+    # asl_gather_kv call over 32 layers x Hk heads stacked as rows (what SnapKV-style compression of
+    # every layer before the selection layer moves in total), indices from this layer's top-k.
+    gather_leg = None
+    if not args.no_batched_gather:
+        n_layers = 32
+        rows = n_layers * sh.Hk
+        try:
+            bctx = asl.Asl(sh.N, rows, n_layers * sh.Hq * sh.W)
+            bp = asl.make_params(n_layers * sh.Hq, rows, sh.d, sh.N, sh.W, sh.S, sh.budget)
+            k_all = torch.empty((rows, sh.N, sh.d), dtype=torch.bfloat16, device=dev).normal_()
+            v_all = torch.empty((rows, sh.N, sh.d), dtype=torch.bfloat16, device=dev).normal_()
+            idx_all = I[:sh.Hk].repeat(n_layers, 1).contiguous()
+            ko = torch.empty((rows, n_idx, sh.d), dtype=torch.bfloat16, device=dev)
+            vo = torch.empty_like(ko)
+            GK = asl.KERNEL_NAMES.index("gather")
+            for _ in range(3):
+                bctx.asl_gather_kv(bp, k_all, v_all, idx_all, rows, n_idx, ko, vo)
+            bctx.asl_profile_enable(1 << GK, 32)
+            for _ in range(20):
+                bctx.asl_gather_kv(bp, k_all, v_all, idx_all, rows, n_idx, ko, vo)
+            torch.cuda.synchronize()
+            g_ms, g_n = bctx.asl_profile_collect(GK)
+            bctx.asl_profile_enable(0, 0)
+            g_bytes = 2 * 2 * rows * n_idx * sh.d * 2 + rows * n_idx * 4      # K,V read + written, indices
+            g_gbs = g_bytes / (g_ms / g_n * 1e-3) / 1e9
+            gather_leg = {"layers": n_layers, "bytes": g_bytes, "avg_launch_ms": round(g_ms / g_n, 5),
+                          "achieved_GBps": round(g_gbs, 1), "frac_of_hbm_peak": round(g_gbs / HBM_PEAK_GBS, 4)}
+            del k_all, v_all, ko, vo
+            bctx.close()
+        except Exception as e:                                # noqa: BLE001 - report, do not hide the headline
+            gather_leg = {"error": str(e)}
+
     cpu = None
     if not args.no_cpu:
         from oracle import asl_oracle as orc
@@ -279,6 +313,7 @@ def main() -> int:
                    "eager_ms_per_step": round(eager_ms_per_step, 5),
                    "step": "asl_layer_step = score_layer + rank_stat(full ring) + select_topk(Hk per-head rows + the all-head row) + gather_kv(K,V per head)"},
         "roofline": roofline, "cpu_baseline": cpu, "lse_supplied": lse_leg,
+        "gather_batched": gather_leg,
     }
     if kernels is not None:
         line["kernels"] = kernels

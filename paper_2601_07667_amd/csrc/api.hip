@@ -22,7 +22,7 @@ struct asl_ctx {
 
 namespace {
 
-constexpr int kMaxSelectRows = 48;
+constexpr int kMaxSelectRows = 1024;   // rows per call (KV heads, or layers x KV heads when batched)
 constexpr int kMaxPoolKernel = 129;
 
 size_t align_up(size_t x) { return (x + 255) & ~size_t(255); }
