@@ -49,7 +49,6 @@ size_t carve(char* base, int32_t max_seq_len, int32_t max_kv_heads, int32_t max_
     w.sort_idx[i] = (uint32_t*)take(N * sizeof(uint32_t));
   }
   w.tile_hist = (uint32_t*)take(256 * sort_tiles * sizeof(uint32_t));   // [tile][256]
-  w.counters = (uint32_t*)take(asl::kCounterWords * sizeof(uint32_t));
   w.sel_hist = (uint32_t*)take(4 * rows * sel_tiles * 256 * sizeof(uint32_t));
   w.sel_state = (uint32_t*)take(4 * rows * 2 * sizeof(uint32_t));
   w.sel_tile_cnt = (uint32_t*)take(rows * sel_tiles * sizeof(uint32_t));
@@ -159,8 +158,8 @@ asl_status asl_create(asl_ctx** out, int device, int32_t max_seq_len, int32_t ma
   }
   carve(static_cast<char*>(ctx->base), max_seq_len, max_kv_heads, max_q_rows, &ctx->ws);
   ctx->ws.prof = nullptr;
-  // tickets, accumulators and select histograms must start at zero; the kernels that use them
-  // leave them at zero again
+  // nothing in the workspace needs an initial value; zero it once so that no run ever reads
+  // uninitialised memory
   e = hipMemset(ctx->base, 0, ctx->bytes);
   if (e != hipSuccess) {
     (void)hipFree(ctx->base);

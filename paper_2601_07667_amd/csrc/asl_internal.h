@@ -56,7 +56,6 @@ struct Workspace {
   uint32_t* sort_key[2];   // [T] ping-pong
   uint32_t* sort_idx[2];   // [T]
   uint32_t* tile_hist;     // [n_tiles][256] per-tile digit histogram of the current sort pass
-  uint32_t* counters;      // small block of zero-initialised tickets / accumulators
   // select
   uint32_t* sel_hist;      // [4 passes][rows][n_tiles][256]
   uint32_t* sel_state;     // [4 passes][rows][2]  {prefix, keys still to take}
@@ -69,10 +68,8 @@ struct Workspace {
 constexpr int kSortTile = 2048;        // elements per radix-sort workgroup tile
 constexpr int kSelTile = 4096;         // elements per select workgroup tile
 constexpr int kMaxChunks = 256;        // key chunks per KV head in scoring pass 1
-constexpr int kCounterWords = 64;
 constexpr int kVarMaxBlocks = 512;     // workgroups of the rank-variance kernel
 
-// counters layout (uint32 words)
 
 hipError_t launch_score(const asl_params& p, const Workspace& ws, const void* q_obs, const void* k,
                         const float* lse, hipStream_t st);
