@@ -22,8 +22,14 @@ namespace asl {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
-constexpr int KT = 64;                        // keys per LDS tile
-constexpr int STAGES = 3;                     // LDS tile buffers: two tiles in flight while one is consumed
+#ifndef ASL_SCORE_KT
+#define ASL_SCORE_KT 64
+#endif
+#ifndef ASL_SCORE_STAGES
+#define ASL_SCORE_STAGES 3
+#endif
+constexpr int KT = ASL_SCORE_KT;              // keys per LDS tile (a multiple of 32)
+constexpr int STAGES = ASL_SCORE_STAGES;      // LDS tile buffers: STAGES-1 tiles in flight while one is consumed
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kNegBig = -1.0e30f;           // finite stand-in for "no maximum yet"
 
@@ -104,24 +110,27 @@ __device__ __forceinline__ void issue_tile_loads(const TilePieces<D, NT>& tp, co
 // still outstanding; they complete in issue order, so everything older than the last CNT is done.
 template <int CNT>
 __device__ __forceinline__ void wait_vmem() {
-  static_assert(CNT >= 0 && CNT < 16, "vmcnt immediate (low 4 bits used)");
-  __builtin_amdgcn_s_waitcnt(0x0F70 | CNT);          // vmcnt(CNT), expcnt/lgkmcnt untouched
+  static_assert(CNT >= 0 && CNT < 64, "vmcnt is a 6-bit count");
+  // vmcnt(CNT): low 4 bits in [3:0], high 2 bits in [15:14]; expcnt / lgkmcnt left at "no wait"
+  __builtin_amdgcn_s_waitcnt(0x0F70 | (CNT & 0xF) | ((CNT >> 4) << 14));
 }
 
 // Loads each wave issues per tile, when that number is the same for every wave (else -1).
 template <int D, int NT>
 constexpr int tile_loads_per_wave() { return ((KT * (D / 8)) % NT == 0) ? (KT * (D / 8)) / NT : -1; }
 
-// Top-of-iteration wait: tile `it` must have landed.  With a uniform per-wave load count the
-// younger tile (if one is in flight) may stay outstanding; otherwise wait for everything.
+// Top-of-iteration wait: the current tile must have landed.  `younger` = tiles issued after it that
+// are still in flight (at most STAGES-2).  With a uniform per-wave load count those may stay
+// outstanding; otherwise wait for everything.
 template <int D, int NT>
-__device__ __forceinline__ void wait_tile(bool younger_in_flight) {
+__device__ __forceinline__ void wait_tile(int younger) {
   constexpr int L = tile_loads_per_wave<D, NT>();
-  if constexpr (L > 0 && L < 16) {
-    if (younger_in_flight) {
-      wait_vmem<L>();
-      return;
-    }
+  static_assert(STAGES >= 2 && STAGES <= 6, "ring depth");
+  if constexpr (L > 0 && L * (STAGES - 2) < 64) {
+    if (STAGES >= 6 && younger >= 4) return wait_vmem<(STAGES >= 6 ? 4 : 0) * L>();
+    if (STAGES >= 5 && younger >= 3) return wait_vmem<(STAGES >= 5 ? 3 : 0) * L>();
+    if (STAGES >= 4 && younger >= 2) return wait_vmem<(STAGES >= 4 ? 2 : 0) * L>();
+    if (STAGES >= 3 && younger >= 1) return wait_vmem<(STAGES >= 3 ? 1 : 0) * L>();
   }
   wait_vmem<0>();
 }
@@ -244,7 +253,7 @@ score_rowstats_kernel(const __bf16* __restrict__ q_obs, const __bf16* __restrict
   float m_run = kNegBig, z_run = 0.f;
   int stage = 0;                                  // buffer that holds tile `tile`
   for (int tile = tile0; tile < tile_end; ++tile) {
-    wait_tile<D, NT>(tile + 1 < tile_end);
+    wait_tile<D, NT>(min(STAGES - 2, tile_end - 1 - tile));
     __syncthreads();      // tile `tile` has landed for every wave; the buffer of tile-1 is free again
     const int free_stage = (stage == 0) ? STAGES - 1 : stage - 1;
     rowstats_tile<D, NT>(lds_k + stage * TILE_ELEMS, lds_k + free_stage * TILE_ELEMS,
@@ -369,7 +378,7 @@ score_colsum_kernel(const __bf16* __restrict__ q_obs, const __bf16* __restrict__
   int stage = 0;                                  // buffer that holds the current tile
   for (int it = 0; it < n_my; ++it) {
     const int tile = tile_end - 1 - it;
-    wait_tile<D, NT>(it + 1 < n_my);
+    wait_tile<D, NT>(min(STAGES - 2, n_my - 1 - it));
     __syncthreads();      // the tile has landed; previous tile's fragment reads and partials are done
     if (it > 0) reduce_store((it - 1) & 1, (tile + 1) * KT);
     const int free_stage = (stage == 0) ? STAGES - 1 : stage - 1;
@@ -459,11 +468,12 @@ bool score_mfma_supported(const asl_params& p) {
 // Key chunks per KV head: one resident round of workgroups, so that no second, partly filled
 // round trails behind.  Tunable through ASL_SCORE_WORKGROUPS (total workgroups per pass).
 int score_chunks(const asl_params& p) {
-  static const int target = [] {
+  static const int forced = [] {
     const char* e = getenv("ASL_SCORE_WORKGROUPS");
     const int v = e ? atoi(e) : 0;
-    return v > 0 ? v : 768;
+    return v > 0 ? v : 0;
   }();
+  const int target = forced ? forced : 768;     // 256 CUs x 3 resident workgroups (measured best)
   const int n_tiles = (p.seq_len + KT - 1) / KT;
   int want = target / p.n_kv_heads;
   if (want > kMaxChunks) want = kMaxChunks;
