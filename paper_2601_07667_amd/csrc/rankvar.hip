@@ -163,7 +163,7 @@ rankvar_final_kernel(int n_parts, int l_obs, int layer_idx, double tau, int push
 
 hipError_t launch_stat_skip(Prof* prof, asl_stat* out, asl_state* state, int layer_idx, int l_obs,
                             int push, hipStream_t st) {
-  ASL_LAUNCH(prof, kKernRingPush, st, stat_skip_kernel, dim3(1), dim3(64), 0, st, out, state, layer_idx,
+  ASL_LAUNCH(prof, kKernRankvarFinal, st, stat_skip_kernel, dim3(1), dim3(64), 0, st, out, state, layer_idx,
              l_obs, push);
   return hipGetLastError();
 }
@@ -174,7 +174,7 @@ hipError_t launch_rankvar(const Workspace& ws, const int32_t* ring, int l_obs, i
   if (blocks > kVarMaxBlocks) blocks = kVarMaxBlocks;
   ASL_LAUNCH(ws.prof, kKernRankvar, st, rankvar_partial_kernel, dim3(blocks), dim3(kVarThreads), 0, st, ring,
              l_obs, T, layer_idx, k, push, state, ws.var_part_num, ws.var_part_cnt);
-  ASL_LAUNCH(ws.prof, kKernRingPush, st, rankvar_final_kernel, dim3(1), dim3(kVarThreads), 0, st, blocks, l_obs,
+  ASL_LAUNCH(ws.prof, kKernRankvarFinal, st, rankvar_final_kernel, dim3(1), dim3(kVarThreads), 0, st, blocks, l_obs,
              layer_idx, tau, push, state, out, ws.var_part_num, ws.var_part_cnt);
   return hipGetLastError();
 }
