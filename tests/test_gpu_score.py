@@ -62,6 +62,13 @@ def test_small_shapes(gpu_device, Hq, Hk, d, N, W):
     _compare(gpu_device, L)
 
 
+@pytest.mark.parametrize("N", [64 * 5 + 16, 64 * 5 + 15, 64 * 5 + 17, 64 * 6 + 32, 64 * 40 + 1])
+def test_key_counts_around_tile_edges(gpu_device, N):
+    """N - W one below / at / one above a multiple of the 64-key tile; several chunks per head."""
+    _compare(gpu_device, _small(4, 2, 128, N, 16, seed=N))
+    _compare(gpu_device, _small(4, 2, 128, N, 16, seed=N + 1), use_lse=True)
+
+
 def test_lse_supplied_mode_and_scale(gpu_device):
     L = _small(8, 2, 128, 5000, 32, seed=3)
     P1, s1 = _compare(gpu_device, L)

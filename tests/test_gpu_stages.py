@@ -83,6 +83,16 @@ def test_rank_is_deterministic(ctx, gpu_device):
     assert torch.equal(a, b)
 
 
+@pytest.mark.parametrize("T", [2048 * 3 - 1, 2048 * 3, 2048 * 3 + 1, 4095, 4096, 4097, 64 * 33 + 7])
+def test_rank_and_select_at_tile_boundaries(ctx, gpu_device, T):
+    """Sizes one below, at and one above multiples of the sort tile (2048) and the select tile (4096)."""
+    rng = np.random.default_rng(T)
+    s = np.round(rng.standard_normal(T), 2).astype(np.float32)            # heavy ties
+    _rank_case(ctx, gpu_device, s)
+    for budget in (9, T // 3 + 8, T + 8):                                   # k = 1, ~T/3, T
+        _select_case(ctx, gpu_device, np.stack([s, -s]), budget, 8)
+
+
 # ----------------------------------------------------------------------------- statistic
 def _stat_case(ctx, dev, R: np.ndarray, l_obs: int, k: int, tau: float, layer_idx: int,
                init_var=None):
