@@ -7,10 +7,11 @@
 // the row statistics, pass 2 streams K again for the normalised column sums.  When the caller
 // hands over the rows' log-sum-exp, pass 1 is skipped.
 //
-// Work split: a workgroup owns one KV head and a contiguous chunk of keys; wave w owns query rows
-// [32w, 32w+32) and keeps their bf16 fragments in registers for the whole kernel; K tiles of 128
-// keys stream global -> LDS directly (double-buffered, XOR-swizzled) and every wave reads all of
-// them as the other MFMA operand (v_mfma_f32_32x32x16_bf16).  Pass 1 puts keys on the
+// Work split: a workgroup owns one KV head and a contiguous chunk of keys; wave w owns RB blocks of
+// 32 query rows (RB = 1 up to M = 128 rows, 2 above) and keeps their bf16 fragments in registers for
+// the whole kernel; K tiles of 64 keys stream global -> LDS directly (ring of 3-4 buffers,
+// XOR-swizzled) and every wave reads all of them as the other MFMA operand
+// (v_mfma_f32_32x32x16_bf16), each fragment once for all its row blocks.  Pass 1 puts keys on the
 // accumulator's register axis (row statistics reduce in-lane), pass 2 puts query rows there
 // (column sums reduce in-lane).  All reductions have a fixed order: results are deterministic.
 #include <cstdlib>
@@ -29,7 +30,13 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 #define ASL_SCORE_STAGES 3
 #endif
 constexpr int KT = ASL_SCORE_KT;              // keys per LDS tile (a multiple of 32)
-constexpr int STAGES = ASL_SCORE_STAGES;      // LDS tile buffers: STAGES-1 tiles in flight while one is consumed
+#ifndef ASL_SCORE_STAGES_RB2
+#define ASL_SCORE_STAGES_RB2 4
+#endif
+// LDS tile buffers of the K ring: STAGES-1 tiles in flight while one is consumed.  RB = 32-row query
+// blocks per wavefront: 1 for M <= 128 query rows (three workgroups per compute unit), 2 above
+// (two larger workgroups per compute unit, hence a deeper ring each).
+template <int RB> constexpr int ring_stages() { return RB > 1 ? ASL_SCORE_STAGES_RB2 : ASL_SCORE_STAGES; }
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kNegBig = -1.0e30f;           // finite stand-in for "no maximum yet"
 
@@ -43,8 +50,8 @@ __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_ex
 __device__ __forceinline__ int acc_row(int r, int half) { return 8 * (r >> 2) + 4 * half + (r & 3); }
 
 // K tile staging: global memory -> LDS directly (global_load_lds_dwordx4: each lane names its own
-// 16-byte global source, the hardware writes lane i's data to  wave base + 16*i  in LDS), two LDS
-// buffers, one workgroup barrier per tile.  The tile is stored unpadded; bank conflicts on the
+// 16-byte global source, the hardware writes lane i's data to  wave base + 16*i  in LDS), a ring of
+// LDS buffers, one workgroup barrier per tile.  The tile is stored unpadded; bank conflicts on the
 // fragment reads are avoided by an XOR swizzle applied on the global side: LDS slot (row r,
 // piece c') holds the row's 16-byte piece  c = c' ^ (r mod CPR).
 // Rows past N are clamped to the last key (they are masked or discarded later).
@@ -122,7 +129,7 @@ constexpr int tile_loads_per_wave() { return ((KT * (D / 8)) % NT == 0) ? (KT * 
 // Top-of-iteration wait: the current tile must have landed.  `younger` = tiles issued after it that
 // are still in flight (at most STAGES-2).  With a uniform per-wave load count those may stay
 // outstanding; otherwise wait for everything.
-template <int D, int NT>
+template <int D, int NT, int STAGES>
 __device__ __forceinline__ void wait_tile(int younger) {
   constexpr int L = tile_loads_per_wave<D, NT>();
   static_assert(STAGES >= 2 && STAGES <= 6, "ring depth");
@@ -145,33 +152,42 @@ __device__ __forceinline__ bf16x8 load_k_frag(const __bf16* buf, int sub, int ln
   return *reinterpret_cast<const bf16x8*>(buf + (r * CPR + cp) * 8);
 }
 
-// QK^T of one 32-key sub-tile against this wave's 32 query rows (d/16 chained MFMAs).
+// QK^T of one 32-key sub-tile against this wave's RB blocks of 32 query rows (d/16 chained MFMAs
+// per block; every K fragment is read from LDS once and used for all RB blocks).
 // KEYS_ON_REGS: accumulator register axis = keys (pass 1), else = query rows (pass 2).
-template <int D, bool KEYS_ON_REGS>
-__device__ __forceinline__ f32x16 mma_subtile(const __bf16* __restrict__ buf, int sub, int ln, int half,
-                                              const bf16x8 (&qf)[D / 16]) {
-  f32x16 acc;
+template <int D, bool KEYS_ON_REGS, int RB>
+__device__ __forceinline__ void mma_subtile(const __bf16* __restrict__ buf, int sub, int ln, int half,
+                                            const bf16x8 (&qf)[RB][D / 16], f32x16 (&acc)[RB]) {
 #pragma unroll
-  for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+  for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[rb][r] = 0.f;
 #pragma unroll
   for (int ks = 0; ks < D / 16; ++ks) {
+#ifdef ASL_DIAG_ONEFRAG   // diagnosis builds only: wrong results, one LDS fragment read per sub-tile
+    const bf16x8 kf = load_k_frag<D>(buf, sub, ln, half, 0);
+#else
     const bf16x8 kf = load_k_frag<D>(buf, sub, ln, half, ks);
-    acc = KEYS_ON_REGS ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], acc, 0, 0, 0)
-                       : __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[ks], kf, acc, 0, 0, 0);
+#endif
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb)
+      acc[rb] = KEYS_ON_REGS ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[rb][ks], acc[rb], 0, 0, 0)
+                             : __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[rb][ks], kf, acc[rb], 0, 0, 0);
   }
-  return acc;
 }
 
-// Query fragments of this wave's 32-row block: lane (ln, half) holds row ln, d = 16*ks + 8*half .. +8.
-#define ASL_LOAD_Q_FRAGS()                                                                      \
-  bf16x8 qf[KS];                                                                                \
-  {                                                                                             \
-    const __bf16* qg_ = q_obs + (int64_t)g * M * D + (int64_t)min(qrow, M - 1) * D + half * 8;  \
-    _Pragma("unroll") for (int ks = 0; ks < KS; ++ks) {                                         \
-      uint4 raw_ = *reinterpret_cast<const uint4*>(qg_ + ks * 16);                              \
-      if (qrow >= M) raw_ = make_uint4(0u, 0u, 0u, 0u);     /* padded rows: zero queries */     \
-      qf[ks] = __builtin_bit_cast(bf16x8, raw_);                                                \
-    }                                                                                           \
+// Query fragments of this wave's RB 32-row blocks (block rb = rows row0 + 32*rb ..): lane (ln, half)
+// holds row ln of each block, d = 16*ks + 8*half .. +8.
+#define ASL_LOAD_Q_FRAGS()                                                                        \
+  bf16x8 qf[RB][KS];                                                                              \
+  _Pragma("unroll") for (int rb = 0; rb < RB; ++rb) {                                             \
+    const int qr_ = row0 + rb * 32 + ln;                                                          \
+    const __bf16* qg_ = q_obs + (int64_t)g * M * D + (int64_t)min(qr_, M - 1) * D + half * 8;     \
+    _Pragma("unroll") for (int ks = 0; ks < KS; ++ks) {                                           \
+      uint4 raw_ = *reinterpret_cast<const uint4*>(qg_ + ks * 16);                                \
+      if (qr_ >= M) raw_ = make_uint4(0u, 0u, 0u, 0u);      /* padded rows: zero queries */       \
+      qf[rb][ks] = __builtin_bit_cast(bf16x8, raw_);                                              \
+    }                                                                                             \
   }
 
 // This file is compiled with NaNs assumed absent, so this is a bare v_max_f32 / v_max3_f32
@@ -181,48 +197,58 @@ __device__ __forceinline__ float max2(float a, float b) { return __builtin_fmaxf
 // One tile of pass 1: start the next tile's LDS-direct loads into `nxt`, then fold the tile in
 // `cur` into the running (max, sum).  The two LDS buffers are distinct restrict pointers so that
 // the compiler knows the fragment reads of `cur` need not wait for the loads into `nxt`.
-template <int D, int NT>
+template <int D, int NT, int RB>
 __device__ __forceinline__ void rowstats_tile(const __bf16* __restrict__ cur, __bf16* __restrict__ nxt,
                                               bool prefetch, const TilePieces<D, NT>& tp, const __bf16* __restrict__ kg, int64_t kst,
-                                              int tile, int N, int T, int wi, int tid, int ln, int half,
-                                              const bf16x8 (&qf)[D / 16], float c1, float& m_run,
-                                              float& z_run) {
-  if (prefetch) issue_tile_loads<D, NT>(tp, kg, kst, (tile + STAGES - 1) * KT, N, nxt, tid);
+                                              int prefetch_key0, int tile, int N, int T, const int (&wi)[RB], int tid, int ln,
+                                              int half, const bf16x8 (&qf)[RB][D / 16], float c1, float (&m_run)[RB],
+                                              float (&z_run)[RB]) {
+  if (prefetch) issue_tile_loads<D, NT>(tp, kg, kst, prefetch_key0, N, nxt, tid);
   const int kbase = tile * KT;
   const bool need_mask = (kbase + KT > T);      // touches the window block or the tail past N
-  // Software pipeline over the four 32-key sub-tiles: the MFMAs of sub-tile s+1 are issued before
+  // Software pipeline over the 32-key sub-tiles: the MFMAs of sub-tile s+1 are issued before
   // the softmax arithmetic of sub-tile s, so the matrix pipe and the vector ALU run side by side.
-  f32x16 acc = mma_subtile<D, true>(cur, 0, ln, half, qf);
+  f32x16 acc[RB];
+  mma_subtile<D, true, RB>(cur, 0, ln, half, qf, acc);
 #pragma unroll
   for (int sub = 0; sub < KT / 32; ++sub) {
-    f32x16 nxt_acc = acc;
-    if (sub + 1 < KT / 32) nxt_acc = mma_subtile<D, true>(cur, sub + 1, ln, half, qf);
-    float x[16];
+    f32x16 nxt_acc[RB];
+    if (sub + 1 < KT / 32) {
+      mma_subtile<D, true, RB>(cur, sub + 1, ln, half, qf, nxt_acc);
+    } else {
 #pragma unroll
-    for (int r = 0; r < 16; ++r) x[r] = acc[r];
-    if (need_mask) {
-      // visible iff key < N and (key < T or key - T <= wi)  <=>  key < min(N, T + wi + 1)
-      const int lim = min(N, T + wi + 1) - (kbase + sub * 32 + 4 * half);
-#pragma unroll
-      for (int r = 0; r < 16; ++r) x[r] = (8 * (r >> 2) + (r & 3) < lim) ? x[r] : -INFINITY;
+      for (int rb = 0; rb < RB; ++rb) nxt_acc[rb] = acc[rb];
     }
-    float mx = x[0];
 #pragma unroll
-    for (int r = 1; r < 16; r += 2) mx = max2(mx, max2(x[r], x[(r + 1) & 15]));
-    const float m_new = max2(m_run, mx * c1);
-    float sum = 0.f;
+    for (int rb = 0; rb < RB; ++rb) {
+      float x[16];
 #pragma unroll
-    for (int r = 0; r < 16; ++r) sum += fast_exp2(fmaf(x[r], c1, -m_new));
-    z_run = z_run * fast_exp2(m_run - m_new) + sum;
-    m_run = m_new;
-    acc = nxt_acc;
+      for (int r = 0; r < 16; ++r) x[r] = acc[rb][r];
+      if (need_mask) {
+        // visible iff key < N and (key < T or key - T <= wi)  <=>  key < min(N, T + wi + 1)
+        const int lim = min(N, T + wi[rb] + 1) - (kbase + sub * 32 + 4 * half);
+#pragma unroll
+        for (int r = 0; r < 16; ++r) x[r] = (8 * (r >> 2) + (r & 3) < lim) ? x[r] : -INFINITY;
+      }
+      float mx = x[0];
+#pragma unroll
+      for (int r = 1; r < 16; r += 2) mx = max2(mx, max2(x[r], x[(r + 1) & 15]));
+      const float m_new = max2(m_run[rb], mx * c1);
+      float sum = 0.f;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) sum += fast_exp2(fmaf(x[r], c1, -m_new));
+      z_run[rb] = z_run[rb] * fast_exp2(m_run[rb] - m_new) + sum;
+      m_run[rb] = m_new;
+    }
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) acc[rb] = nxt_acc[rb];
   }
 }
 
 // ---------------------------------------------------------------------------------------------
 // Pass 1: per-row running (max, sum) over this workgroup's key chunk, in the log2 domain.
 // row_part[((g*n_chunks + chunk)*M + row)*2 + {0,1}] = (m, z) with  sum_j 2^(c1*l_j) = z * 2^m.
-template <int D, int NW>
+template <int D, int NW, int RB>
 __global__ void __launch_bounds__(NW * 64)
 score_rowstats_kernel(const __bf16* __restrict__ q_obs, const __bf16* __restrict__ k, int64_t ksh,
                       int64_t kst, int Hk, int M, int W, int N, int tiles_per_chunk, int n_chunks,
@@ -230,13 +256,16 @@ score_rowstats_kernel(const __bf16* __restrict__ q_obs, const __bf16* __restrict
   constexpr int NT = NW * 64;
   constexpr int KS = D / 16;
   constexpr int TILE_ELEMS = KT * D;
+  constexpr int STAGES = ring_stages<RB>();
   __shared__ __attribute__((aligned(16))) __bf16 lds_k[STAGES * TILE_ELEMS];
 
   const int g = blockIdx.x % Hk, chunk = blockIdx.x / Hk;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, ln = lane & 31, half = lane >> 5;
   const int T = N - W;
-  const int qrow = wave * 32 + ln;
-  const int wi = qrow % W;                      // window row of this lane's query row
+  const int row0 = wave * 32 * RB;              // first query row of this wave
+  int wi[RB];                                   // window row of this lane's query row, per block
+#pragma unroll
+  for (int rb = 0; rb < RB; ++rb) wi[rb] = (row0 + rb * 32 + ln) % W;
   const __bf16* kg = k + (int64_t)g * ksh;
   const int n_tiles_total = (N + KT - 1) / KT;
   const int tile0 = chunk * tiles_per_chunk;
@@ -250,26 +279,35 @@ score_rowstats_kernel(const __bf16* __restrict__ q_obs, const __bf16* __restrict
   for (int j = 0; j < STAGES - 1; ++j)
     if (tile0 + j < tile_end) issue_tile_loads<D, NT>(tp, kg, kst, (tile0 + j) * KT, N, lds_k + j * TILE_ELEMS, tid);
 
-  float m_run = kNegBig, z_run = 0.f;
+  float m_run[RB], z_run[RB];
+#pragma unroll
+  for (int rb = 0; rb < RB; ++rb) {
+    m_run[rb] = kNegBig;
+    z_run[rb] = 0.f;
+  }
   int stage = 0;                                  // buffer that holds tile `tile`
   for (int tile = tile0; tile < tile_end; ++tile) {
-    wait_tile<D, NT>(min(STAGES - 2, tile_end - 1 - tile));
+    wait_tile<D, NT, STAGES>(min(STAGES - 2, tile_end - 1 - tile));
     __syncthreads();      // tile `tile` has landed for every wave; the buffer of tile-1 is free again
     const int free_stage = (stage == 0) ? STAGES - 1 : stage - 1;
-    rowstats_tile<D, NT>(lds_k + stage * TILE_ELEMS, lds_k + free_stage * TILE_ELEMS,
-                         tile + STAGES - 1 < tile_end, tp, kg, kst, tile, N, T, wi, tid, ln, half, qf, c1, m_run,
-                         z_run);
+    rowstats_tile<D, NT, RB>(lds_k + stage * TILE_ELEMS, lds_k + free_stage * TILE_ELEMS,
+                             tile + STAGES - 1 < tile_end, tp, kg, kst, (tile + STAGES - 1) * KT, tile, N, T, wi, tid,
+                             ln, half, qf, c1, m_run, z_run);
     stage = (stage + 1 == STAGES) ? 0 : stage + 1;
   }
-  // the two lane halves hold disjoint keys of the same query row
-  const float m_o = __shfl_xor(m_run, 32), z_o = __shfl_xor(z_run, 32);
-  const float m = max2(m_run, m_o);
-  const float za = z_run * fast_exp2(m_run - m), zb = z_o * fast_exp2(m_o - m);
-  const float z = (half == 0) ? (za + zb) : (zb + za);
-  if (half == 0 && qrow < M) {
-    float* dst = row_part + ((int64_t)(g * n_chunks + chunk) * M + qrow) * 2;
-    dst[0] = m;
-    dst[1] = z;
+#pragma unroll
+  for (int rb = 0; rb < RB; ++rb) {
+    // the two lane halves hold disjoint keys of the same query row
+    const float m_o = __shfl_xor(m_run[rb], 32), z_o = __shfl_xor(z_run[rb], 32);
+    const float m = max2(m_run[rb], m_o);
+    const float za = z_run[rb] * fast_exp2(m_run[rb] - m), zb = z_o * fast_exp2(m_o - m);
+    const float z = (half == 0) ? (za + zb) : (zb + za);
+    const int qrow = row0 + rb * 32 + ln;
+    if (half == 0 && qrow < M) {
+      float* dst = row_part + ((int64_t)(g * n_chunks + chunk) * M + qrow) * 2;
+      dst[0] = m;
+      dst[1] = z;
+    }
   }
 }
 
@@ -303,32 +341,41 @@ score_combine_kernel(const float* __restrict__ row_part, int Hk, int M, int n_ch
 }
 
 // One tile of pass 2: start the next tile's loads into `nxt`, then the column partial sums of
-// this wave's 32 rows for the 128 keys in `cur` (written to red_w[0..127]).
-template <int D, int NT>
+// this wave's 32*RB rows for the KT keys in `cur` (written to red_w[0..KT-1]).
+template <int D, int NT, int RB>
 __device__ __forceinline__ void colsum_tile(const __bf16* __restrict__ cur, __bf16* __restrict__ nxt,
                                             bool prefetch, const TilePieces<D, NT>& tp, const __bf16* __restrict__ kg, int64_t kst,
                                             int prefetch_key0, int N, int tid, int ln, int half,
-                                            const bf16x8 (&qf)[D / 16], const float (&rc)[16], float c1,
+                                            const bf16x8 (&qf)[RB][D / 16], const float (&rc)[RB][16], float c1,
                                             float* __restrict__ red_w) {
   if (prefetch) issue_tile_loads<D, NT>(tp, kg, kst, prefetch_key0, N, nxt, tid);
-  f32x16 acc = mma_subtile<D, false>(cur, 0, ln, half, qf);
+  f32x16 acc[RB];
+  mma_subtile<D, false, RB>(cur, 0, ln, half, qf, acc);
 #pragma unroll
   for (int sub = 0; sub < KT / 32; ++sub) {
-    f32x16 nxt_acc = acc;
-    if (sub + 1 < KT / 32) nxt_acc = mma_subtile<D, false>(cur, sub + 1, ln, half, qf);   // overlaps the exps below
+    f32x16 nxt_acc[RB];
+    if (sub + 1 < KT / 32) {
+      mma_subtile<D, false, RB>(cur, sub + 1, ln, half, qf, nxt_acc);   // overlaps the exps below
+    } else {
+#pragma unroll
+      for (int rb = 0; rb < RB; ++rb) nxt_acc[rb] = acc[rb];
+    }
     float cs = 0.f;
 #pragma unroll
-    for (int r = 0; r < 16; ++r) cs += fast_exp2(fmaf(acc[r], c1, -rc[r]));
+    for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) cs += fast_exp2(fmaf(acc[rb][r], c1, -rc[rb][r]));
     const float other = __shfl_xor(cs, 32);
     if (half == 0) red_w[sub * 32 + ln] = cs + other;
-    acc = nxt_acc;
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) acc[rb] = nxt_acc[rb];
   }
 }
 
 // ---------------------------------------------------------------------------------------------
 // Pass 2: u_group[g][j] = sum over the M rows of 2^(c1*l_rj - rc_r),  j < T,
 // rc_r = rc_mul * row_const[g*M + r]  (log2-domain offset that already contains log2 Z_r).
-template <int D, int NW>
+template <int D, int NW, int RB>
 __global__ void __launch_bounds__(NW * 64)
 score_colsum_kernel(const __bf16* __restrict__ q_obs, const __bf16* __restrict__ k, int64_t ksh,
                     int64_t kst, int Hk, int M, int N, int T, int tiles_per_chunk, float c1,
@@ -336,25 +383,28 @@ score_colsum_kernel(const __bf16* __restrict__ q_obs, const __bf16* __restrict__
   constexpr int NT = NW * 64;
   constexpr int KS = D / 16;
   constexpr int TILE_ELEMS = KT * D;
+  constexpr int STAGES = ring_stages<RB>();
   __shared__ __attribute__((aligned(16))) __bf16 lds_k[STAGES * TILE_ELEMS];
   __shared__ float red[2][NW][KT];              // per-wave column partials, double-buffered
 
   const int g = blockIdx.x % Hk, chunk = blockIdx.x / Hk;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, ln = lane & 31, half = lane >> 5;
-  const int qrow = wave * 32 + ln;
+  const int row0 = wave * 32 * RB;              // first query row of this wave
   const __bf16* kg = k + (int64_t)g * ksh;
   const int n_tiles_total = (T + KT - 1) / KT;
   const int tile0 = chunk * tiles_per_chunk;
   const int tile_end = min(tile0 + tiles_per_chunk, n_tiles_total);
 
   ASL_LOAD_Q_FRAGS();
-  float rc[16];
+  float rc[RB][16];
 #pragma unroll
-  for (int r = 0; r < 16; ++r) {
-    const int row = wave * 32 + acc_row(r, half);
-    const float v = row_const[(int64_t)g * M + min(row, M - 1)] * rc_mul;
-    rc[r] = (row < M) ? v : INFINITY;                    // padded rows add 2^-inf = 0
-  }
+  for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int row = row0 + rb * 32 + acc_row(r, half);
+      const float v = row_const[(int64_t)g * M + min(row, M - 1)] * rc_mul;
+      rc[rb][r] = (row < M) ? v : INFINITY;              // padded rows add 2^-inf = 0
+    }
   TilePieces<D, NT> tp;
   tp.init(kst, tid);
   // The chunk is walked from its last tile to its first: pass 1 walked it first to last, so the
@@ -378,12 +428,13 @@ score_colsum_kernel(const __bf16* __restrict__ q_obs, const __bf16* __restrict__
   int stage = 0;                                  // buffer that holds the current tile
   for (int it = 0; it < n_my; ++it) {
     const int tile = tile_end - 1 - it;
-    wait_tile<D, NT>(min(STAGES - 2, n_my - 1 - it));
+    wait_tile<D, NT, STAGES>(min(STAGES - 2, n_my - 1 - it));
     __syncthreads();      // the tile has landed; previous tile's fragment reads and partials are done
     if (it > 0) reduce_store((it - 1) & 1, (tile + 1) * KT);
     const int free_stage = (stage == 0) ? STAGES - 1 : stage - 1;
-    colsum_tile<D, NT>(lds_k + stage * TILE_ELEMS, lds_k + free_stage * TILE_ELEMS, it + STAGES - 1 < n_my,
-                       tp, kg, kst, (tile - (STAGES - 1)) * KT, N, tid, ln, half, qf, rc, c1, &red[it & 1][wave][0]);
+    colsum_tile<D, NT, RB>(lds_k + stage * TILE_ELEMS, lds_k + free_stage * TILE_ELEMS, it + STAGES - 1 < n_my,
+                           tp, kg, kst, (tile - (STAGES - 1)) * KT, N, tid, ln, half, qf, rc, c1,
+                           &red[it & 1][wave][0]);
     stage = (stage + 1 == STAGES) ? 0 : stage + 1;
   }
   if (n_my > 0) {
@@ -465,6 +516,9 @@ bool score_mfma_supported(const asl_params& p) {
   return p.dtype == ASL_BF16 && (p.head_dim == 64 || p.head_dim == 128) && M <= 256;
 }
 
+// Query-row blocks per wavefront: one up to M = 128 rows per KV head, two above.
+static int score_row_blocks(int M) { return M > 128 ? 2 : 1; }
+
 // Key chunks per KV head: one resident round of workgroups, so that no second, partly filled
 // round trails behind.  Tunable through ASL_SCORE_WORKGROUPS (total workgroups per pass).
 int score_chunks(const asl_params& p) {
@@ -473,7 +527,9 @@ int score_chunks(const asl_params& p) {
     const int v = e ? atoi(e) : 0;
     return v > 0 ? v : 0;
   }();
-  const int target = forced ? forced : 768;     // 256 CUs x 3 resident workgroups (measured best)
+  const int M = (p.n_q_heads / p.n_kv_heads) * p.window;
+  // 256 CUs x resident workgroups per CU (three with one row block per wavefront, two with two)
+  const int target = forced ? forced : (score_row_blocks(M) > 1 ? 512 : 768);
   const int n_tiles = (p.seq_len + KT - 1) / KT;
   int want = target / p.n_kv_heads;
   if (want > kMaxChunks) want = kMaxChunks;
@@ -483,7 +539,7 @@ int score_chunks(const asl_params& p) {
   return (n_tiles + tpc - 1) / tpc;
 }
 
-template <int D, int NW>
+template <int D, int NW, int RB>
 static hipError_t launch_score_mfma(const asl_params& p, const Workspace& ws, const __bf16* q,
                                     const __bf16* k, const float* lse, float c1, hipStream_t st) {
   const int Hk = p.n_kv_heads, M = (p.n_q_heads / Hk) * p.window, N = p.seq_len, T = N - p.window;
@@ -491,7 +547,7 @@ static hipError_t launch_score_mfma(const asl_params& p, const Workspace& ws, co
   const int n_tiles1 = (N + KT - 1) / KT;
   const int tpc1 = (n_tiles1 + n_chunks - 1) / n_chunks;
   if (!lse) {
-    ASL_LAUNCH(ws.prof, kKernRowstats, st, (score_rowstats_kernel<D, NW>), dim3(Hk * n_chunks), dim3(NW * 64), 0, st, q, k,
+    ASL_LAUNCH(ws.prof, kKernRowstats, st, (score_rowstats_kernel<D, NW, RB>), dim3(Hk * n_chunks), dim3(NW * 64), 0, st, q, k,
                        p.k_stride_head, p.k_stride_tok, Hk, M, p.window, N, tpc1, n_chunks, c1,
                        ws.row_part);
     const int rows = Hk * M;
@@ -501,25 +557,26 @@ static hipError_t launch_score_mfma(const asl_params& p, const Workspace& ws, co
   const int n_tiles2 = (T + KT - 1) / KT;
   const int tpc2 = (n_tiles2 + n_chunks - 1) / n_chunks;
   const int n_chunks2 = (n_tiles2 + tpc2 - 1) / tpc2;
-  ASL_LAUNCH(ws.prof, kKernColsum, st, (score_colsum_kernel<D, NW>), dim3(Hk * n_chunks2), dim3(NW * 64), 0, st, q, k,
+  ASL_LAUNCH(ws.prof, kKernColsum, st, (score_colsum_kernel<D, NW, RB>), dim3(Hk * n_chunks2), dim3(NW * 64), 0, st, q, k,
                      p.k_stride_head, p.k_stride_tok, Hk, M, N, T, tpc2, c1,
                      lse ? lse : ws.row_const, lse ? kLog2e : 1.0f, ws.u_group);
   return hipGetLastError();
 }
 
+// M <= 128: wavefronts of one 32-row block, NW = ceil(M / 32); above: two blocks each, NW = ceil(M / 64).
 template <int D>
-static hipError_t dispatch_nw(int nw, const asl_params& p, const Workspace& ws, const __bf16* q,
+static hipError_t dispatch_nw(int M, const asl_params& p, const Workspace& ws, const __bf16* q,
                               const __bf16* k, const float* lse, float c1, hipStream_t st) {
-  switch (nw) {
-    case 1: return launch_score_mfma<D, 1>(p, ws, q, k, lse, c1, st);
-    case 2: return launch_score_mfma<D, 2>(p, ws, q, k, lse, c1, st);
-    case 3: return launch_score_mfma<D, 3>(p, ws, q, k, lse, c1, st);
-    case 4: return launch_score_mfma<D, 4>(p, ws, q, k, lse, c1, st);
-    case 5: return launch_score_mfma<D, 5>(p, ws, q, k, lse, c1, st);
-    case 6: return launch_score_mfma<D, 6>(p, ws, q, k, lse, c1, st);
-    case 7: return launch_score_mfma<D, 7>(p, ws, q, k, lse, c1, st);
-    default: return launch_score_mfma<D, 8>(p, ws, q, k, lse, c1, st);
+  if (score_row_blocks(M) == 1) {
+    switch ((M + 31) / 32) {
+      case 1: return launch_score_mfma<D, 1, 1>(p, ws, q, k, lse, c1, st);
+      case 2: return launch_score_mfma<D, 2, 1>(p, ws, q, k, lse, c1, st);
+      case 3: return launch_score_mfma<D, 3, 1>(p, ws, q, k, lse, c1, st);
+      default: return launch_score_mfma<D, 4, 1>(p, ws, q, k, lse, c1, st);
+    }
   }
+  return (M + 63) / 64 == 3 ? launch_score_mfma<D, 3, 2>(p, ws, q, k, lse, c1, st)
+                            : launch_score_mfma<D, 4, 2>(p, ws, q, k, lse, c1, st);
 }
 
 template <typename TIn>
@@ -544,11 +601,10 @@ hipError_t launch_score(const asl_params& p, const Workspace& ws, const void* q_
   const float c1 = scale * kLog2e;
   const int M = (p.n_q_heads / p.n_kv_heads) * p.window;
   if (score_mfma_supported(p) && !(p.flags & ASL_FLAG_GENERIC_SCORE)) {
-    const int nw = (M + 31) / 32;
     const __bf16* q = static_cast<const __bf16*>(q_obs);
     const __bf16* kk = static_cast<const __bf16*>(k);
-    return p.head_dim == 128 ? dispatch_nw<128>(nw, p, ws, q, kk, lse, c1, st)
-                             : dispatch_nw<64>(nw, p, ws, q, kk, lse, c1, st);
+    return p.head_dim == 128 ? dispatch_nw<128>(M, p, ws, q, kk, lse, c1, st)
+                             : dispatch_nw<64>(M, p, ws, q, kk, lse, c1, st);
   }
   if (p.dtype == ASL_BF16)
     return launch_score_generic<__bf16>(p, ws, static_cast<const __bf16*>(q_obs),
