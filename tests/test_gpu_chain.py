@@ -99,6 +99,15 @@ def test_config_chain(gpu_device, cfg):
     _check_layer(L, out)
 
 
+def test_one_million_tokens(gpu_device):
+    """A context four times the longest one of the paper's workloads (N = 2^20, two KV heads):
+    every kernel runs with several thousand tiles per row and 64-bit offsets are exercised."""
+    sh = synth.Shape(Hq=4, Hk=2, d=128, N=1 << 20, W=32, S=7, budget=8192)
+    L = synth.iid_layer(sh, 77, name="1M")
+    print("chain 1M", flush=True)
+    _check_layer(L, _pipeline(gpu_device, L))
+
+
 def test_config1_bf16_chain(gpu_device):
     sh = synth.shape_of(1)
     sh.dtype = "bf16"
