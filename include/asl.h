@@ -130,6 +130,8 @@ asl_status asl_rank(asl_ctx* ctx, const float* s, int32_t T, int32_t* rank_out, 
  *   ranks; first evaluation sets state->init_var; selected = (var_top / init_var < tau).
  *   With layer_idx < l_min or fewer than two rows: out->evaluated = 0 and nothing else changes.
  *   On selection the ring is released (state->n_valid_rows = 0).
+ *   `out` may be device memory or page-locked host memory that the device can address (the
+ *   kernel then writes the record straight to the host; read it after synchronising the stream).
  * Limits: n^2 * T^3 / 4 must fit in 64 bits (ASL_EUNSUPPORTED otherwise). */
 asl_status asl_rankvar(asl_ctx* ctx, const int32_t* rank_ring, int32_t l_obs, int32_t T,
                        int32_t layer_idx, int32_t l_min, int32_t k, double tau,

@@ -65,8 +65,14 @@ struct Workspace {
   Prof* prof;              // null unless profiling is enabled
 };
 
-constexpr int kSortTile = 2048;        // elements per radix-sort workgroup tile
-constexpr int kSelTile = 4096;         // elements per select workgroup tile
+#ifndef ASL_SORT_TILE
+#define ASL_SORT_TILE 2048
+#endif
+#ifndef ASL_SEL_TILE
+#define ASL_SEL_TILE 4096
+#endif
+constexpr int kSortTile = ASL_SORT_TILE;   // elements per radix-sort workgroup tile (a multiple of 256)
+constexpr int kSelTile = ASL_SEL_TILE;     // elements per select workgroup tile (a multiple of 256)
 constexpr int kMaxChunks = 256;        // key chunks per KV head in scoring pass 1
 constexpr int kVarMaxBlocks = 512;     // workgroups of the rank-variance kernel
 

@@ -272,3 +272,23 @@ def test_argument_errors(ctx, gpu_device):
     assert ctx.lib.asl_create(C.byref(h), 0, 1, 8, 8) == asl.ASL_EINVAL
     assert ctx.lib.asl_create(C.byref(h), 99, 1024, 8, 8) == asl.ASL_EHIP
     assert "idx_rows" in ctx.lib.asl_last_error(ctx.h).decode() or True
+
+def test_stat_written_straight_to_pinned_host_memory(ctx, gpu_device):
+    """The decision record may live in page-locked host memory: the statistic kernel writes it there
+    and the host reads it after a stream synchronisation, with no copy of its own."""
+    import torch
+    T, l_obs, k = 5000, 4, 300
+    rng = np.random.default_rng(5)
+    ring = torch.zeros((l_obs, T), dtype=torch.int32, device=gpu_device)
+    state = asl.new_state(gpu_device)
+    stat_dev = asl.new_stat(gpu_device)
+    stat_host = torch.zeros(stat_dev.numel(), dtype=torch.uint8).pin_memory()
+    p = asl.make_params(4, 2, 64, T + 8, 8, 7, k + 8)
+    for layer in range(l_obs + 2):
+        s = torch.from_numpy(rng.standard_normal(T).astype(np.float32)).to(gpu_device)
+        st2 = state.clone()
+        ctx.asl_rank_stat(p, s, layer, 0, l_obs, 0.0, ring.clone(), st2, stat_dev)
+        ctx.asl_rank_stat(p, s, layer, 0, l_obs, 0.0, ring, state, stat_host)
+        torch.cuda.synchronize()
+        assert bytes(stat_host.numpy().tobytes()) == bytes(stat_dev.cpu().numpy().tobytes())
+    assert asl.AslStat.from_buffer_copy(bytes(stat_host.numpy().tobytes())).evaluated == 1
