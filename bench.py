@@ -28,6 +28,21 @@ PMC_TRAFFIC_BYTES = {3: int((131260.0 * 2.0 + 4095.0 * 1.0) * 1024)}
 MFMA_BF16_PEAK_TFLOPS = 2500.0   # dense bf16
 
 
+def attention_lse(q, k, sh):
+    """Input preparation for the one-pass mode: the natural-log sum-exp of every window row's
+    scaled, causally masked logits, [Hq, W] fp32.  In a prefill this comes out of the layer's
+    attention kernel; here plain torch ops stand in for that kernel (not part of the timed path)."""
+    import torch
+    G, W, N, T = sh.G, sh.W, sh.N, sh.T
+    out = torch.empty((sh.Hq, W), dtype=torch.float32, device=q.device)
+    causal = torch.ones((W, W), dtype=torch.bool, device=q.device).triu(1)     # key index > row index
+    for h in range(sh.Hq):
+        logits = (q[h].float() @ k[h // G].float().T) * sh.scale              # [W, N]
+        logits[:, T:].masked_fill_(causal, float("-inf"))
+        out[h] = torch.logsumexp(logits, dim=1)
+    return out
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -41,6 +56,8 @@ def main() -> int:
     ap.add_argument("--copy-ref", action="store_true",
                     help="also run a plain 256 MiB device copy (a reference of known traffic for counter runs)")
     ap.add_argument("--one-stream", action="store_true", help="no fork: rank/statistic and top-k/gather back to back")
+    ap.add_argument("--join-each-step", action="store_true",
+                    help="wait for a step's top-k + compaction before the next step starts (no overlap across steps)")
     ap.add_argument("--no-batched-gather", action="store_true", help="skip the 32-layer batched KV-compaction leg")
     ap.add_argument("--breakdown", action="store_true", help="also time every kernel with events (untimed extra loop)")
     args = ap.parse_args()
@@ -61,6 +78,8 @@ def main() -> int:
     sh = L.shape
     ctx = asl.Asl(sh.N, sh.Hk + 1, sh.Hq * sh.W)
     p = asl.make_params(sh.Hq, sh.Hk, sh.d, sh.N, sh.W, sh.S, sh.budget)
+    # steps that leave their top-k + compaction running on the second stream while the next step scores
+    p_defer = asl.make_params(sh.Hq, sh.Hk, sh.d, sh.N, sh.W, sh.S, sh.budget, flags=asl.ASL_FLAG_DEFER_JOIN)
     up = lambda x: torch.from_numpy(x).to(dev).to(torch.bfloat16).contiguous()
     q, k, v = up(L.q_obs), up(L.k), up(L.v)
     # Every layer of a real prefill has its own K/V, so consecutive steps must not find the previous
@@ -81,10 +100,8 @@ def main() -> int:
     Vc = torch.empty_like(Kc)
     lses = [None] * N_SETS
     if args.lse:
-        from oracle import asl_oracle as orc          # input preparation for the one-pass mode only
         for j in range(N_SETS):
-            kj = ks[j].float().cpu().numpy()
-            lses[j] = torch.from_numpy(orc.row_lse(L.q_obs, kj, sh.W).astype(np.float32)).to(dev)
+            lses[j] = attention_lse(q, ks[j], sh)
     lse = lses[0]
 
     # Fill the rank ring with L_obs-1 earlier "layers" (perturbed scores) so that every timed step
@@ -111,12 +128,13 @@ def main() -> int:
             ctx.asl_select_topk(p, PS, sh.Hk + 1, I)
             ctx.asl_gather_kv(p, kk, vv, I, sh.Hk, n_idx, Kc, Vc)
         else:
-            ctx.asl_layer_step(p, q, kk, vv, layer_idx, 0, sh.L_obs, 0.0, PS, ring, state, stat, I, Kc, Vc,
-                               lse=lses[layer_idx % N_SETS])
+            ctx.asl_layer_step(p if args.join_each_step else p_defer, q, kk, vv, layer_idx, 0, sh.L_obs, 0.0, PS,
+                               ring, state, stat, I, Kc, Vc, lse=lses[layer_idx % N_SETS])
 
     for _ in range(args.warmup):
         step(layer)
         layer += 1
+    ctx.asl_join()
     torch.cuda.synchronize()
     if args.copy_ref:
         # 64 Mi fp32 elements = 256 MiB read + 256 MiB written by one elementwise copy kernel
@@ -144,10 +162,12 @@ def main() -> int:
             while asl.read_struct(state, asl.AslState).last_layer % sh.L_obs != sh.L_obs - 1:
                 nxt = asl.read_struct(state, asl.AslState).last_layer + 1
                 step(nxt)
+                ctx.asl_join()
                 torch.cuda.synchronize()
             with torch.cuda.graph(graph, stream=cap_stream):
                 for j in range(sh.L_obs):
                     step(layer + j)
+                ctx.asl_join()                         # a capture must end with every forked stream joined
             for _ in range(2):
                 graph.replay()
         torch.cuda.synchronize()
@@ -161,6 +181,7 @@ def main() -> int:
         for _ in range(args.steps):
             step(layer)
             layer += 1
+        ctx.asl_join()
         torch.cuda.synchronize()
         t1 = time.perf_counter()
     st = asl.read_struct(stat, asl.AslStat)
@@ -177,6 +198,7 @@ def main() -> int:
     for _ in range(args.steps):
         step(layer)
         layer += 1
+    ctx.asl_join()
     torch.cuda.synchronize()
     e1 = time.perf_counter()
     dom_ms, dom_n = ctx.asl_profile_collect(DOM)
@@ -190,24 +212,44 @@ def main() -> int:
     # kernel already has), so K is streamed once per layer instead of twice.  Eager launches.
     lse_leg = None
     if not args.lse and not args.no_lse_leg:
-        from oracle import asl_oracle as orc          # input preparation only (row normalisers)
         for j in range(N_SETS):
-            lses[j] = torch.from_numpy(orc.row_lse(L.q_obs, ks[j].float().cpu().numpy(), sh.W)
-                                       .astype(np.float32)).to(dev)
+            lses[j] = attention_lse(q, ks[j], sh)
         for _ in range(8):
             step(layer)
             layer += 1
+        ctx.asl_join()
         torch.cuda.synchronize()
         l0 = time.perf_counter()
         for _ in range(args.steps):
             step(layer)
             layer += 1
+        ctx.asl_join()
         torch.cuda.synchronize()
         l1 = time.perf_counter()
         lse_ms = (l1 - l0) * 1e3 / args.steps
         lse_leg = {"ms_per_step": round(lse_ms, 5), "value": round(sh.N / (lse_ms * 1e-3), 1),
                    "note": "lse [Hq,W] supplied by the caller: one pass over K"}
         lses = [None] * N_SETS
+
+    # Extra leg: a layer before the selection layer only scores, ranks and evaluates the statistic
+    # (no top-k, no compaction).  Eager launches of the two single calls.
+    ordinary_leg = None
+    if not args.no_lse_leg:
+        def ordinary(layer_idx: int) -> None:
+            ctx.asl_score_layer(p, q, ks[layer_idx % N_SETS], P, s)
+            ctx.asl_rank_stat(p, s, layer_idx, 0, sh.L_obs, 0.0, ring, state, stat)
+        for _ in range(8):
+            ordinary(layer)
+            layer += 1
+        torch.cuda.synchronize()
+        o0 = time.perf_counter()
+        for _ in range(args.steps):
+            ordinary(layer)
+            layer += 1
+        torch.cuda.synchronize()
+        o_ms = (time.perf_counter() - o0) * 1e3 / args.steps
+        ordinary_leg = {"ms_per_step": round(o_ms, 5), "value": round(sh.N / (o_ms * 1e-3), 1),
+                        "note": "score + pool + rank + statistic only (a layer that does not select), eager"}
 
     # Algorithmic HBM bytes of one pass-2 launch: every past key once (bf16), the window queries,
     # and the group-summed column sums written once.
@@ -231,6 +273,7 @@ def main() -> int:
         for _ in range(n_b):
             step(layer)
             layer += 1
+        ctx.asl_join()
         torch.cuda.synchronize()
         kernels = {}
         for i, name in enumerate(asl.KERNEL_NAMES):
@@ -309,11 +352,14 @@ def main() -> int:
                    "budget": sh.budget, "L_obs": sh.L_obs,
                    "score_mode": "lse supplied (one K pass)" if args.lse else "self-contained (two K passes)",
                    "launch": ("HIP graph replay (8 layers per graph)" if use_graph else "eager launches from Python")
-                             + ("" if args.one_stream else "; rank+statistic and top-k+gather on two streams"),
+                             + ("" if args.one_stream else "; rank+statistic and top-k+gather on two streams")
+                             + ("" if (args.one_stream or args.join_each_step) else
+                                "; a step's top-k+gather may still run while the next step scores (joined before its "
+                                "scores are overwritten and at the end of the timed region)"),
                    "eager_ms_per_step": round(eager_ms_per_step, 5),
                    "step": "asl_layer_step = score_layer + rank_stat(full ring) + select_topk(Hk per-head rows + the all-head row) + gather_kv(K,V per head)"},
         "roofline": roofline, "cpu_baseline": cpu, "lse_supplied": lse_leg,
-        "gather_batched": gather_leg,
+        "ordinary_layer": ordinary_leg, "gather_batched": gather_leg,
     }
     if kernels is not None:
         line["kernels"] = kernels

@@ -65,6 +65,9 @@ typedef struct {
 
 /* Score with the plain fp32-FMA kernels even where the MFMA kernels apply (an on-GPU cross-check). */
 #define ASL_FLAG_GENERIC_SCORE 1
+/* asl_layer_step only: return without waiting for the top-k + compaction work on the context's
+ * second stream (see asl_layer_step and asl_join). */
+#define ASL_FLAG_DEFER_JOIN 2
 
 /* Cross-layer state of Alg. 2 (init_var and the fill level of the rank cache).  24-byte device
  * struct owned by the caller; all-zero bytes = fresh sequence.  The library updates it. */
@@ -176,12 +179,24 @@ asl_status asl_gather_rows(asl_ctx* ctx, const void* src, int64_t src_row_stride
  *           (to be used only when out->selected is set).
  *   k_out, v_out [Hk, k+W, d] out: K[I], V[I] per head; pass k_out = NULL to skip the compaction.
  * The ctx must have been created with max_kv_heads >= Hk + 1.  Other arguments as in the single
- * calls.  Not to be overlapped with any other call on the same ctx. */
+ * calls.  Not to be overlapped with any other call on the same ctx.
+ * With ASL_FLAG_DEFER_JOIN in params->flags the call returns as soon as ranking + statistic are
+ * queued on `stream`; idx_out, k_out and v_out are then complete only after asl_join.  The next
+ * asl_layer_step on the ctx joins by itself before it overwrites `scores` (so in a layer loop the
+ * top-k + compaction of one layer overlaps the scoring of the next); until the join, `scores`, k, v
+ * and the three outputs of the deferred call must not be written or freed, and no other entry point
+ * may be used on the ctx.  Call asl_join before reading the outputs and before ending a stream
+ * capture (asl_destroy waits for the second stream by itself). */
 asl_status asl_layer_step(asl_ctx* ctx, const asl_params* params, const void* q_obs, const void* k,
                           const void* v, const float* lse, int32_t layer_idx, int32_t l_min,
                           int32_t l_obs, double tau, float* scores, int32_t* rank_ring,
                           asl_state* state, asl_stat* out, int32_t* idx_out, void* k_out, void* v_out,
                           void* stream);
+
+/* Makes `stream` wait for the second-stream work of the last asl_layer_step issued with
+ * ASL_FLAG_DEFER_JOIN (no-op if there is none).  Sec. 4.2 "Prefilling": only the decision is needed
+ * before the next layer starts; the compacted KV of a layer is needed at decoding time. */
+asl_status asl_join(asl_ctx* ctx, void* stream);
 
 /* Measurement aid (not a step of the paper's method; for callers that time the kernels of the
  * calls above).  Kernel ids: 0 score row statistics (pass 1), 1 its combine, 2 score column sums

@@ -16,11 +16,12 @@ LIB_PATH = os.environ.get("ASL_LIBRARY_PATH") or os.path.join(_PKG, "libasl.so")
 ASL_OK, ASL_EINVAL, ASL_ENOMEM, ASL_EHIP, ASL_EUNSUPPORTED = 0, -1, -2, -3, -4
 ASL_BF16, ASL_F32 = 0, 1
 ASL_FLAG_GENERIC_SCORE = 1
+ASL_FLAG_DEFER_JOIN = 2
 _STATUS = {0: "ASL_OK", -1: "ASL_EINVAL", -2: "ASL_ENOMEM", -3: "ASL_EHIP", -4: "ASL_EUNSUPPORTED"}
 
 EXPORTS = ["asl_create", "asl_destroy", "asl_last_error", "asl_workspace_bytes", "asl_score_layer",
            "asl_pool", "asl_rank", "asl_rankvar", "asl_rank_stat", "asl_select_topk", "asl_gather_kv",
-           "asl_gather_rows", "asl_layer_step", "asl_profile_enable", "asl_profile_collect"]
+           "asl_gather_rows", "asl_layer_step", "asl_join", "asl_profile_enable", "asl_profile_collect"]
 
 
 class AslParams(C.Structure):
@@ -88,6 +89,8 @@ def load() -> C.CDLL:
     lib.asl_layer_step.argtypes = [vp, C.POINTER(AslParams), vp, vp, vp, vp, i32, i32, i32, C.c_double,
                                    vp, vp, vp, vp, vp, vp, vp, vp]
     lib.asl_layer_step.restype = C.c_int
+    lib.asl_join.argtypes = [vp, vp]
+    lib.asl_join.restype = C.c_int
     lib.asl_profile_enable.argtypes = [vp, C.c_uint32, i32]
     lib.asl_profile_enable.restype = C.c_int
     lib.asl_profile_collect.argtypes = [vp, i32, C.POINTER(C.c_double), C.POINTER(i32)]
@@ -174,6 +177,9 @@ class Asl:
                                             layer_idx, l_min, l_obs, tau, _ptr(scores), _ptr(rank_ring),
                                             _ptr(state), _ptr(out), _ptr(idx_out), _ptr(k_out), _ptr(v_out),
                                             _stream()))
+
+    def asl_join(self) -> None:
+        self._check(self.lib.asl_join(self.h, _stream()))
 
     def asl_profile_enable(self, kernel_mask: int, max_records: int) -> None:
         self._check(self.lib.asl_profile_enable(self.h, kernel_mask, max_records))

@@ -17,6 +17,7 @@ struct asl_ctx {
   asl::Prof prof;
   hipStream_t side;          // second stream of asl_layer_step's fork/join (default priority)
   hipEvent_t ev_fork, ev_join;
+  bool side_pending;         // a deferred asl_layer_step left work on `side` that nobody has waited for yet
   char err[256];
 };
 
@@ -167,6 +168,7 @@ asl_status asl_create(asl_ctx** out, int device, int32_t max_seq_len, int32_t ma
     return ASL_EHIP;
   }
   ctx->side = nullptr;
+  ctx->side_pending = false;
   ctx->ev_fork = ctx->ev_join = nullptr;
   e = hipStreamCreateWithFlags(&ctx->side, hipStreamNonBlocking);
   if (e == hipSuccess) e = hipEventCreateWithFlags(&ctx->ev_fork, hipEventDisableTiming);
@@ -265,8 +267,10 @@ asl_status asl_destroy(asl_ctx* ctx) {
 
 const char* asl_last_error(const asl_ctx* ctx) { return ctx ? ctx->err : "null context"; }
 
-asl_status asl_score_layer(asl_ctx* ctx, const asl_params* p, const void* q_obs, const void* k,
-                           const float* lse, float* p_head, float* s_all, void* stream) {
+// Scoring + pooling.  With wait_side set, the pooling kernel (the first one that overwrites the
+// score rows) is ordered behind the side-stream work a deferred asl_layer_step left behind.
+static asl_status score_layer_impl(asl_ctx* ctx, const asl_params* p, const void* q_obs, const void* k,
+                                   const float* lse, float* p_head, float* s_all, void* stream, bool wait_side) {
   asl_status st = check_params(ctx, p);
   if (st != ASL_OK) return st;
   if (!q_obs || !k || !p_head || !s_all) return fail(ctx, ASL_EINVAL, "null tensor pointer");
@@ -282,10 +286,20 @@ asl_status asl_score_layer(asl_ctx* ctx, const asl_params* p, const void* q_obs,
   hipStream_t hs = static_cast<hipStream_t>(stream);
   hipError_t e = asl::launch_score(*p, ctx->ws, q_obs, k, lse, hs);
   if (e != hipSuccess) return hip_fail(ctx, e, "score launch");
+  if (wait_side && ctx->side_pending) {
+    e = hipStreamWaitEvent(hs, ctx->ev_join, 0);
+    if (e != hipSuccess) return hip_fail(ctx, e, "join");
+    ctx->side_pending = false;
+  }
   const int T = p->seq_len - p->window;
   e = asl::launch_pool(ctx->ws.prof, ctx->ws.u_group, p->n_kv_heads, T, p->pool_kernel, p_head, s_all, hs);
   if (e != hipSuccess) return hip_fail(ctx, e, "pool launch");
   return ASL_OK;
+}
+
+asl_status asl_score_layer(asl_ctx* ctx, const asl_params* p, const void* q_obs, const void* k,
+                           const float* lse, float* p_head, float* s_all, void* stream) {
+  return score_layer_impl(ctx, p, q_obs, k, lse, p_head, s_all, stream, false);
 }
 
 asl_status asl_pool(asl_ctx* ctx, const float* u, int32_t rows, int32_t T, int32_t S, float* p_out,
@@ -441,7 +455,7 @@ asl_status asl_layer_step(asl_ctx* ctx, const asl_params* p, const void* q_obs, 
   float* p_head = scores;
   float* s_all = scores + (int64_t)Hk * T;
   hipStream_t hs = static_cast<hipStream_t>(stream);
-  st = asl_score_layer(ctx, p, q_obs, k, lse, p_head, s_all, stream);
+  st = score_layer_impl(ctx, p, q_obs, k, lse, p_head, s_all, stream, true);
   if (st != ASL_OK) return st;
   DeviceGuard guard(ctx->device);
   if (guard.err != hipSuccess) return hip_fail(ctx, guard.err, "set device");
@@ -452,13 +466,30 @@ asl_status asl_layer_step(asl_ctx* ctx, const asl_params* p, const void* q_obs, 
   asl_status st_side = asl_select_topk(ctx, p, scores, Hk + 1, idx_out, ctx->side);
   if (st_side == ASL_OK && k_out != nullptr)
     st_side = asl_gather_kv(ctx, p, k, v, idx_out, Hk, k_sel + p->window, k_out, v_out, ctx->side);
-  // join even if a launch failed, so that the side stream never stays forked (e.g. under capture)
   e = hipEventRecord(ctx->ev_join, ctx->side);
   asl_status st_main = asl_rank_stat(ctx, p, s_all, layer_idx, l_min, l_obs, tau, rank_ring, state, out, stream);
-  if (e == hipSuccess) e = hipStreamWaitEvent(hs, ctx->ev_join, 0);
+  // join now, or leave it to the next asl_layer_step / asl_join; a failed launch always joins, so
+  // that the side stream never stays forked (e.g. under capture)
+  const bool defer = (p->flags & ASL_FLAG_DEFER_JOIN) && st_side == ASL_OK && st_main == ASL_OK && e == hipSuccess;
+  if (defer) {
+    ctx->side_pending = true;
+  } else if (e == hipSuccess) {
+    e = hipStreamWaitEvent(hs, ctx->ev_join, 0);
+  }
   if (st_side != ASL_OK) return st_side;
   if (st_main != ASL_OK) return st_main;
   if (e != hipSuccess) return hip_fail(ctx, e, "join");
+  return ASL_OK;
+}
+
+asl_status asl_join(asl_ctx* ctx, void* stream) {
+  if (!ctx) return ASL_EINVAL;
+  if (!ctx->side_pending) return ASL_OK;
+  DeviceGuard guard(ctx->device);
+  if (guard.err != hipSuccess) return hip_fail(ctx, guard.err, "set device");
+  hipError_t e = hipStreamWaitEvent(static_cast<hipStream_t>(stream), ctx->ev_join, 0);
+  if (e != hipSuccess) return hip_fail(ctx, e, "join");
+  ctx->side_pending = false;
   return ASL_OK;
 }
 

@@ -77,6 +77,29 @@ constexpr int kMaxChunks = 256;        // key chunks per KV head in scoring pass
 constexpr int kVarMaxBlocks = 512;     // workgroups of the rank-variance kernel
 
 
+// 256-bin digit histogram of a workgroup in LDS, kept in 8 copies (lane % 8 picks the copy, rows
+// padded to 257 words so that equal digits in different copies fall into different banks): when
+// most keys share a digit - the exponent byte of similar scores, or all-equal scores - a single
+// copy would serialise every lane of a wavefront on one address.
+constexpr int kHistCopies = 8;
+constexpr int kHistStride = 257;
+constexpr int kHistWords = kHistCopies * kHistStride;
+
+#ifdef __HIPCC__
+__device__ __forceinline__ void hist_clear(uint32_t* h, int tid, int n_threads) {
+  for (int i = tid; i < kHistWords; i += n_threads) h[i] = 0;
+}
+__device__ __forceinline__ void hist_add(uint32_t* h, int tid, uint32_t digit) {
+  atomicAdd(&h[(tid & (kHistCopies - 1)) * kHistStride + digit], 1u);
+}
+__device__ __forceinline__ uint32_t hist_total(const uint32_t* h, int digit) {
+  uint32_t t = 0;
+#pragma unroll
+  for (int c = 0; c < kHistCopies; ++c) t += h[c * kHistStride + digit];
+  return t;
+}
+#endif
+
 hipError_t launch_score(const asl_params& p, const Workspace& ws, const void* q_obs, const void* k,
                         const float* lse, hipStream_t st);
 hipError_t launch_pool(Prof* prof, const float* u, int rows, int T, int S, float* p_out, float* s_out,

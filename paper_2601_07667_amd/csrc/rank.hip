@@ -28,9 +28,9 @@ template <bool FIRST>
 __global__ void __launch_bounds__(kSortThreads)
 sort_hist_kernel(const float* __restrict__ s, const uint32_t* __restrict__ keys_in, int T, int shift,
                  uint32_t* __restrict__ tile_hist) {
-  __shared__ uint32_t h[256];
+  __shared__ uint32_t h[kHistWords];
   const int tid = threadIdx.x;
-  h[tid] = 0;
+  hist_clear(h, tid, kSortThreads);
   __syncthreads();
   const int base = blockIdx.x * kSortTile;
   uint32_t key[kSortRounds];
@@ -43,10 +43,10 @@ sort_hist_kernel(const float* __restrict__ s, const uint32_t* __restrict__ keys_
 #pragma unroll
   for (int i = 0; i < kSortRounds; ++i) {
     const int e = base + i * kSortThreads + tid;
-    if (e < T) atomicAdd(&h[(key[i] >> shift) & 255u], 1u);
+    if (e < T) hist_add(h, tid, (key[i] >> shift) & 255u);
   }
   __syncthreads();
-  tile_hist[(int64_t)blockIdx.x * 256 + tid] = h[tid];
+  tile_hist[(int64_t)blockIdx.x * 256 + tid] = hist_total(h, tid);
 }
 
 // Stable scatter of one tile.  Every workgroup derives its own exclusive offsets from the

@@ -109,7 +109,7 @@ __global__ void __launch_bounds__(kSelThreads)
 select_hist_kernel(const float* __restrict__ scores, int T, int n_tiles, int rows, int pass, int k,
                    uint32_t* __restrict__ hist, uint32_t* __restrict__ state,
                    uint32_t* __restrict__ tile_lt) {
-  __shared__ uint32_t h[256];
+  __shared__ uint32_t h[kHistWords];
   __shared__ uint32_t sm[16];
   const int tid = threadIdx.x, row = blockIdx.y, tile = blockIdx.x;
   const int shift = 24 - 8 * pass;
@@ -140,16 +140,16 @@ select_hist_kernel(const float* __restrict__ scores, int T, int n_tiles, int row
       }
     }
   }
-  h[tid] = 0;
+  hist_clear(h, tid, kSelThreads);
   __syncthreads();
 #pragma unroll
   for (int i = 0; i < E; ++i) {
     const int e = base + i * kSelThreads + tid;
     const bool match = (pass == 0) || ((key[i] >> (shift + 8)) == prefix);
-    if (e < T && match) atomicAdd(&h[(key[i] >> shift) & 255u], 1u);
+    if (e < T && match) hist_add(h, tid, (key[i] >> shift) & 255u);
   }
   __syncthreads();
-  hist[(((int64_t)pass * rows + row) * n_tiles + tile) * 256 + tid] = h[tid];
+  hist[(((int64_t)pass * rows + row) * n_tiles + tile) * 256 + tid] = hist_total(h, tid);
 }
 
 // Ordered compaction: position of a kept token = (#below before it) + min(#equal before it, k_rem).

@@ -377,46 +377,62 @@ def test_ring_restart_and_cyclic_continuity(gpu_device):
     ctx.close()
 
 
-def test_layer_step_graph_replay_matches_eager(gpu_device):
+@pytest.mark.parametrize("defer", [False, True])
+def test_layer_step_graph_replay_matches_eager(gpu_device, defer):
     """Capture L_obs consecutive asl_layer_step calls in a HIP graph, replay it several times with
-    eager work and synchronisations in between, and compare every replay with the eager result."""
+    eager work and synchronisations in between, and compare every replay with the eager result.
+    defer: the steps leave their top-k + compaction on the second stream (ASL_FLAG_DEFER_JOIN) and all
+    layers share ONE score buffer, so a step's top-k must have read it before the next step's pooling
+    overwrites it; the reference is the same sequence with every step joined."""
     import torch
     sh = synth.Shape(Hq=8, Hk=2, d=128, N=6000, W=32, S=7, budget=256, L_obs=4, L_min=0)
     layers = [synth.iid_layer(sh, 100 + j) for j in range(sh.L_obs)]
     dev = gpu_device
     ctx = asl.Asl(sh.N, sh.Hk + 1, sh.Hq * sh.W)
     p = gu.params_of(sh)
+    p_defer = gu.params_of(sh, flags=asl.ASL_FLAG_DEFER_JOIN)
     T, n_idx = sh.T, sh.k + sh.W
     qs = [gu.to_dev(L.q_obs, "bf16", dev) for L in layers]
     kss = [gu.to_dev(L.k, "bf16", dev) for L in layers]
     vss = [gu.to_dev(L.v, "bf16", dev) for L in layers]
+    n_score_bufs = 1 if defer else sh.L_obs
 
     def buffers():
-        return dict(scores=torch.zeros((sh.L_obs, sh.Hk + 1, T), dtype=torch.float32, device=dev),
+        return dict(scores=torch.zeros((n_score_bufs, sh.Hk + 1, T), dtype=torch.float32, device=dev),
                     ring=torch.zeros((sh.L_obs, T), dtype=torch.int32, device=dev),
                     state=asl.new_state(dev), stats=torch.zeros((sh.L_obs, 40), dtype=torch.uint8, device=dev),
                     I=torch.zeros((sh.L_obs, sh.Hk + 1, n_idx), dtype=torch.int32, device=dev),
                     K=torch.zeros((sh.L_obs, sh.Hk, n_idx, sh.d), dtype=torch.bfloat16, device=dev),
                     V=torch.zeros((sh.L_obs, sh.Hk, n_idx, sh.d), dtype=torch.bfloat16, device=dev))
 
-    def trip(b, first_layer):
+    def trip(b, first_layer, params):
         for j in range(sh.L_obs):
-            ctx.asl_layer_step(p, qs[j], kss[j], vss[j], first_layer + j, 0, sh.L_obs, 0.0, b["scores"][j], b["ring"],
-                               b["state"], b["stats"][j], b["I"][j], b["K"][j], b["V"][j])
+            ctx.asl_layer_step(params, qs[j], kss[j], vss[j], first_layer + j, 0, sh.L_obs, 0.0,
+                               b["scores"][j % n_score_bufs], b["ring"], b["state"], b["stats"][j], b["I"][j],
+                               b["K"][j], b["V"][j])
+        ctx.asl_join()                               # no-op unless the steps were deferred
 
     ref = buffers()
-    trip(ref, 0)
-    trip(ref, sh.L_obs)                              # second trip: the ring is full, statistic over 4 rows
+    trip(ref, 0, p)
+    trip(ref, sh.L_obs, p)                           # second trip: the ring is full, statistic over 4 rows
     torch.cuda.synchronize()
+    pg = p_defer if defer else p
+    if defer:                                        # eager deferred steps first
+        e = buffers()
+        trip(e, 0, pg)
+        trip(e, sh.L_obs, pg)
+        torch.cuda.synchronize()
+        for name in ("scores", "ring", "I", "K", "V", "stats"):
+            assert torch.equal(e[name], ref[name]), f"eager deferred steps: {name} differs"
     g = buffers()
-    trip(g, 0)                                       # warm the ring eagerly, then capture the second trip
+    trip(g, 0, pg)                                   # warm the ring eagerly, then capture the second trip
     torch.cuda.synchronize()
     cap = torch.cuda.Stream()
     cap.wait_stream(torch.cuda.current_stream())
     graph = torch.cuda.CUDAGraph()
     with torch.cuda.stream(cap):
         with torch.cuda.graph(graph, stream=cap):
-            trip(g, sh.L_obs)
+            trip(g, sh.L_obs, pg)
     torch.cuda.synchronize()
     for rep in range(3):
         for t in (g["scores"], g["I"], g["K"], g["V"], g["stats"]):
