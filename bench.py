@@ -56,8 +56,9 @@ def main() -> int:
     ap.add_argument("--copy-ref", action="store_true",
                     help="also run a plain 256 MiB device copy (a reference of known traffic for counter runs)")
     ap.add_argument("--one-stream", action="store_true", help="no fork: rank/statistic and top-k/gather back to back")
-    ap.add_argument("--join-each-step", action="store_true",
-                    help="wait for a step's top-k + compaction before the next step starts (no overlap across steps)")
+    ap.add_argument("--defer-join", action="store_true",
+                    help="leave a step's top-k + compaction on the second stream while the next step scores "
+                         "(ASL_FLAG_DEFER_JOIN); by default every step joins before it returns")
     ap.add_argument("--no-batched-gather", action="store_true", help="skip the 32-layer batched KV-compaction leg")
     ap.add_argument("--breakdown", action="store_true", help="also time every kernel with events (untimed extra loop)")
     args = ap.parse_args()
@@ -128,7 +129,7 @@ def main() -> int:
             ctx.asl_select_topk(p, PS, sh.Hk + 1, I)
             ctx.asl_gather_kv(p, kk, vv, I, sh.Hk, n_idx, Kc, Vc)
         else:
-            ctx.asl_layer_step(p if args.join_each_step else p_defer, q, kk, vv, layer_idx, 0, sh.L_obs, 0.0, PS,
+            ctx.asl_layer_step(p_defer if args.defer_join else p, q, kk, vv, layer_idx, 0, sh.L_obs, 0.0, PS,
                                ring, state, stat, I, Kc, Vc, lse=lses[layer_idx % N_SETS])
 
     for _ in range(args.warmup):
@@ -353,7 +354,7 @@ def main() -> int:
                    "score_mode": "lse supplied (one K pass)" if args.lse else "self-contained (two K passes)",
                    "launch": ("HIP graph replay (8 layers per graph)" if use_graph else "eager launches from Python")
                              + ("" if args.one_stream else "; rank+statistic and top-k+gather on two streams")
-                             + ("" if (args.one_stream or args.join_each_step) else
+                             + ("" if (args.one_stream or not args.defer_join) else
                                 "; a step's top-k+gather may still run while the next step scores (joined before its "
                                 "scores are overwritten and at the end of the timed region)"),
                    "eager_ms_per_step": round(eager_ms_per_step, 5),

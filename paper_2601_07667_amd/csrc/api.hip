@@ -463,11 +463,12 @@ asl_status asl_layer_step(asl_ctx* ctx, const asl_params* p, const void* q_obs, 
   hipError_t e = hipEventRecord(ctx->ev_fork, hs);
   if (e == hipSuccess) e = hipStreamWaitEvent(ctx->side, ctx->ev_fork, 0);
   if (e != hipSuccess) return hip_fail(ctx, e, "fork");
+  // the longer chain (ranking + statistic) is queued first and stays on the caller's stream
+  asl_status st_main = asl_rank_stat(ctx, p, s_all, layer_idx, l_min, l_obs, tau, rank_ring, state, out, stream);
   asl_status st_side = asl_select_topk(ctx, p, scores, Hk + 1, idx_out, ctx->side);
   if (st_side == ASL_OK && k_out != nullptr)
     st_side = asl_gather_kv(ctx, p, k, v, idx_out, Hk, k_sel + p->window, k_out, v_out, ctx->side);
   e = hipEventRecord(ctx->ev_join, ctx->side);
-  asl_status st_main = asl_rank_stat(ctx, p, s_all, layer_idx, l_min, l_obs, tau, rank_ring, state, out, stream);
   // join now, or leave it to the next asl_layer_step / asl_join; a failed launch always joins, so
   // that the side stream never stays forked (e.g. under capture)
   const bool defer = (p->flags & ASL_FLAG_DEFER_JOIN) && st_side == ASL_OK && st_main == ASL_OK && e == hipSuccess;
