@@ -69,6 +69,12 @@ def test_key_counts_around_tile_edges(gpu_device, N):
     _compare(gpu_device, _small(4, 2, 128, N, 16, seed=N + 1), use_lse=True)
 
 
+@pytest.mark.parametrize("d,dtype", [(96, "bf16"), (256, "bf16"), (80, "f32")])
+def test_other_head_dims_take_the_plain_kernels(gpu_device, d, dtype):
+    """Head dimensions outside {64, 128} are scored by the plain-FMA kernels."""
+    _compare(gpu_device, _small(4, 2, d, 700, 8, dtype=dtype, seed=d))
+
+
 def test_lse_supplied_mode_and_scale(gpu_device):
     L = _small(8, 2, 128, 5000, 32, seed=3)
     P1, s1 = _compare(gpu_device, L)
