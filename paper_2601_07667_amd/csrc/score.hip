@@ -190,6 +190,54 @@ __device__ __forceinline__ void mma_subtile(const __bf16* __restrict__ buf, int 
     }                                                                                             \
   }
 
+
+// Share of the key tiles a workgroup takes.  All workgroups of a pass are resident at once (one
+// round), block b being the (b / n_cu)-th workgroup placed on its compute unit; on this part the
+// first-placed workgroup of a compute unit progresses fastest and the last-placed slowest
+// (measured finish times 0.70 : 0.85 : 0.98 of the kernel with three per unit, 0.76 : 0.98 with two).
+// With three per unit (M <= 128) the kernels are bound by the unit's share of the HBM stream and
+// weighting the shares does not shorten them, so the weights are equal; with two per unit (M > 128)
+// the arithmetic is not hidden any more, the second workgroup ends up alone on its unit for the last
+// quarter of the kernel, and giving the first one a larger share is worth 4-5 %.  Weights in 1/1024,
+// tunable at build time.
+#ifndef ASL_SCORE_W3
+#define ASL_SCORE_W3 1024, 1024, 1024
+#endif
+#ifndef ASL_SCORE_W2
+#define ASL_SCORE_W2 1250, 798
+#endif
+struct ChunkRange {
+  int tile0, tile_end;
+};
+__device__ __forceinline__ int pick3(int i, int a, int b, int c) { return i == 0 ? a : (i == 1 ? b : c); }
+__device__ __forceinline__ int pick2(int i, int a, int b) { return i == 0 ? a : b; }
+// Tiles [tile0, tile_end) of chunk `chunk` (0 .. n_chunks-1) of KV head g; the chunks of a head tile
+// [0, n_tiles) exactly, in order.  (Selects instead of indexed tables: no private memory.)
+__device__ __forceinline__ ChunkRange chunk_range(int chunk, int g, int Hk, int n_chunks, int n_tiles, int n_cu) {
+  const int grid = n_chunks * Hk;
+  const int n_slots = (grid + n_cu - 1) / n_cu;
+  // cumulative weight of this head's chunks 0 .. c-1: chunk c' is block c'*Hk + g, placed as number
+  // (c'*Hk + g) / n_cu on its compute unit
+  auto cum = [&](int c) -> int {
+    if (n_slots != 2 && n_slots != 3) return 1024 * c;
+    // chunks with (c'*Hk + g) < n_cu*(s+1)  <=>  c' < ceil((n_cu*(s+1) - g) / Hk)
+    const int u0 = min(max((n_cu - g + Hk - 1) / Hk, 0), c);
+    const int u1 = (n_slots == 2) ? c : min(max((2 * n_cu - g + Hk - 1) / Hk, u0), c);
+    const int w0 = (n_slots == 3) ? pick3(0, ASL_SCORE_W3) : pick2(0, ASL_SCORE_W2);
+    const int w1 = (n_slots == 3) ? pick3(1, ASL_SCORE_W3) : pick2(1, ASL_SCORE_W2);
+    const int w2 = pick3(2, ASL_SCORE_W3);
+    return w0 * u0 + w1 * (u1 - u0) + w2 * (c - u1);      // < 2^21 for n_chunks <= 256
+  };
+  // Boundaries in fp32 (a 64-bit integer division would cost microseconds at the start of every
+  // workgroup): neighbours evaluate the same expression on the same inputs, so their shared
+  // boundary is the same number, and any monotone rounding gives a valid partition.
+  const float per_weight = (float)n_tiles / (float)cum(n_chunks);
+  ChunkRange r;
+  r.tile0 = min((int)((float)cum(chunk) * per_weight), n_tiles);
+  r.tile_end = (chunk + 1 == n_chunks) ? n_tiles : min((int)((float)cum(chunk + 1) * per_weight), n_tiles);
+  return r;
+}
+
 // This file is compiled with NaNs assumed absent, so this is a bare v_max_f32 / v_max3_f32
 // (inputs are finite or -inf here).
 __device__ __forceinline__ float max2(float a, float b) { return __builtin_fmaxf(a, b); }
@@ -251,7 +299,7 @@ __device__ __forceinline__ void rowstats_tile(const __bf16* __restrict__ cur, __
 template <int D, int NW, int RB>
 __global__ void __launch_bounds__(NW * 64)
 score_rowstats_kernel(const __bf16* __restrict__ q_obs, const __bf16* __restrict__ k, int64_t ksh,
-                      int64_t kst, int Hk, int M, int W, int N, int tiles_per_chunk, int n_chunks,
+                      int64_t kst, int Hk, int M, int W, int N, int n_cu, int n_chunks,
                       float c1, float* __restrict__ row_part) {
   constexpr int NT = NW * 64;
   constexpr int KS = D / 16;
@@ -267,9 +315,8 @@ score_rowstats_kernel(const __bf16* __restrict__ q_obs, const __bf16* __restrict
 #pragma unroll
   for (int rb = 0; rb < RB; ++rb) wi[rb] = (row0 + rb * 32 + ln) % W;
   const __bf16* kg = k + (int64_t)g * ksh;
-  const int n_tiles_total = (N + KT - 1) / KT;
-  const int tile0 = chunk * tiles_per_chunk;
-  const int tile_end = min(tile0 + tiles_per_chunk, n_tiles_total);
+  const ChunkRange cr = chunk_range(chunk, g, Hk, n_chunks, (N + KT - 1) / KT, n_cu);
+  const int tile0 = cr.tile0, tile_end = cr.tile_end;
 
   ASL_LOAD_Q_FRAGS();
   TilePieces<D, NT> tp;
@@ -378,7 +425,7 @@ __device__ __forceinline__ void colsum_tile(const __bf16* __restrict__ cur, __bf
 template <int D, int NW, int RB>
 __global__ void __launch_bounds__(NW * 64)
 score_colsum_kernel(const __bf16* __restrict__ q_obs, const __bf16* __restrict__ k, int64_t ksh,
-                    int64_t kst, int Hk, int M, int N, int T, int tiles_per_chunk, float c1,
+                    int64_t kst, int Hk, int M, int N, int T, int n_cu, float c1,
                     const float* __restrict__ row_const, float rc_mul, float* __restrict__ u_group) {
   constexpr int NT = NW * 64;
   constexpr int KS = D / 16;
@@ -391,9 +438,8 @@ score_colsum_kernel(const __bf16* __restrict__ q_obs, const __bf16* __restrict__
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, ln = lane & 31, half = lane >> 5;
   const int row0 = wave * 32 * RB;              // first query row of this wave
   const __bf16* kg = k + (int64_t)g * ksh;
-  const int n_tiles_total = (T + KT - 1) / KT;
-  const int tile0 = chunk * tiles_per_chunk;
-  const int tile_end = min(tile0 + tiles_per_chunk, n_tiles_total);
+  const ChunkRange cr = chunk_range(chunk, g, Hk, (int)(gridDim.x / Hk), (T + KT - 1) / KT, n_cu);
+  const int tile0 = cr.tile0, tile_end = cr.tile_end;
 
   ASL_LOAD_Q_FRAGS();
   float rc[RB][16];
@@ -539,26 +585,36 @@ int score_chunks(const asl_params& p) {
   return (n_tiles + tpc - 1) / tpc;
 }
 
+// Compute units of the current device (256 on MI355X).
+static int device_cu_count() {
+  static const int n = [] {
+    int dev = 0, v = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v < 1)
+      v = 256;
+    return v;
+  }();
+  return n;
+}
+
 template <int D, int NW, int RB>
 static hipError_t launch_score_mfma(const asl_params& p, const Workspace& ws, const __bf16* q,
                                     const __bf16* k, const float* lse, float c1, hipStream_t st) {
   const int Hk = p.n_kv_heads, M = (p.n_q_heads / Hk) * p.window, N = p.seq_len, T = N - p.window;
   const int n_chunks = score_chunks(p);
-  const int n_tiles1 = (N + KT - 1) / KT;
-  const int tpc1 = (n_tiles1 + n_chunks - 1) / n_chunks;
+  const int n_cu = device_cu_count();
   if (!lse) {
     ASL_LAUNCH(ws.prof, kKernRowstats, st, (score_rowstats_kernel<D, NW, RB>), dim3(Hk * n_chunks), dim3(NW * 64), 0, st, q, k,
-                       p.k_stride_head, p.k_stride_tok, Hk, M, p.window, N, tpc1, n_chunks, c1,
+                       p.k_stride_head, p.k_stride_tok, Hk, M, p.window, N, n_cu, n_chunks, c1,
                        ws.row_part);
     const int rows = Hk * M;
     ASL_LAUNCH(ws.prof, kKernCombine, st, score_combine_kernel, dim3((rows + 3) / 4), dim3(256), 0, st, ws.row_part,
                        Hk, M, n_chunks, ws.row_const);
   }
   const int n_tiles2 = (T + KT - 1) / KT;
-  const int tpc2 = (n_tiles2 + n_chunks - 1) / n_chunks;
-  const int n_chunks2 = (n_tiles2 + tpc2 - 1) / tpc2;
+  const int n_chunks2 = n_chunks < n_tiles2 ? n_chunks : n_tiles2;
   ASL_LAUNCH(ws.prof, kKernColsum, st, (score_colsum_kernel<D, NW, RB>), dim3(Hk * n_chunks2), dim3(NW * 64), 0, st, q, k,
-                     p.k_stride_head, p.k_stride_tok, Hk, M, N, T, tpc2, c1,
+                     p.k_stride_head, p.k_stride_tok, Hk, M, N, T, n_cu, c1,
                      lse ? lse : ws.row_const, lse ? kLog2e : 1.0f, ws.u_group);
   return hipGetLastError();
 }
