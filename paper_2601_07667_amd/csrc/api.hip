@@ -108,6 +108,8 @@ asl_status check_params(asl_ctx* ctx, const asl_params* p) {
     return fail(ctx, ASL_EINVAL, "budget must exceed the window (budget=%d W=%d)", p->budget, p->window);
   if (p->dtype != ASL_BF16 && p->dtype != ASL_F32)
     return fail(ctx, ASL_EUNSUPPORTED, "dtype %d not supported", p->dtype);
+  if (p->flags & ~(ASL_FLAG_GENERIC_SCORE | ASL_FLAG_DEFER_JOIN))
+    return fail(ctx, ASL_EINVAL, "unknown bits in flags (0x%x)", (unsigned)p->flags);
   if (p->pool_kernel > kMaxPoolKernel)
     return fail(ctx, ASL_EUNSUPPORTED, "pool kernel S > %d not supported", kMaxPoolKernel);
   if (p->seq_len > ctx->max_seq_len || p->n_kv_heads > ctx->max_kv_heads ||
