@@ -150,9 +150,10 @@ def main() -> int:
     # holds L_obs consecutive layers (one trip round the rank ring), which takes the host's launch
     # cost out of the measurement; --eager launches every kernel from Python instead.
     use_graph = not args.eager
-    if use_graph and args.steps % sh.L_obs != 0:
-        print(f"bench.py: with graph replay --steps must be a multiple of L_obs={sh.L_obs}", file=sys.stderr)
-        return 2
+    if use_graph and (args.steps % sh.L_obs != 0 or args.steps < sh.L_obs):
+        print(f"bench.py: --steps {args.steps} is not a multiple of L_obs={sh.L_obs} (one graph holds L_obs "
+              f"layers): timing eager launches instead", file=sys.stderr)
+        use_graph = False
     if use_graph:
         layer = ((layer + sh.L_obs - 1) // sh.L_obs) * sh.L_obs      # graph starts on ring row 0
         cap_stream = torch.cuda.Stream()
