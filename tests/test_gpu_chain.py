@@ -16,6 +16,8 @@ def _rank_order_consistent(rank_gpu: np.ndarray, s_ref: np.ndarray, what: str):
     """Tokens taken in GPU rank order must have non-increasing oracle scores up to the tolerance."""
     T = s_ref.shape[0]
     assert np.array_equal(np.sort(rank_gpu), np.arange(T)), f"{what}: ranks are not a permutation"
+    if T < 2:
+        return
     order = np.empty(T, dtype=np.int64)
     order[rank_gpu] = np.arange(T)
     so = s_ref[order]
@@ -106,6 +108,18 @@ def test_one_million_tokens(gpu_device):
     L = synth.iid_layer(sh, 77, name="1M")
     print("chain 1M", flush=True)
     _check_layer(L, _pipeline(gpu_device, L))
+
+
+@pytest.mark.parametrize("N,W,budget", [(17, 16, 64), (40, 8, 4096), (65, 64, 65)])
+def test_degenerate_sizes_chain(gpu_device, N, W, budget):
+    """One past token (T = 1), a budget above the sequence length (everything is kept) and
+    k = 1: the whole chain on shapes where every stage degenerates."""
+    sh = synth.Shape(Hq=4, Hk=2, d=64, N=N, W=W, S=7, budget=budget)
+    L = synth.iid_layer(sh, N, name=f"tiny-{N}-{W}-{budget}")
+    out = _pipeline(gpu_device, L)
+    _check_layer(L, out)
+    if budget >= N:
+        np.testing.assert_array_equal(out["I_all"], np.arange(N))
 
 
 def test_config1_bf16_chain(gpu_device):
