@@ -22,7 +22,7 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0            # MI355X published HBM3E bandwidth
 # HBM traffic of one launch of the pass-2 kernel at workload C3, from two rocprofv3 --pmc runs
-# (profiles/score_c3_128k_counters.md): FETCH_SIZE 131260.0 and WRITE_SIZE 4095.0 KiB-units per
+# (profiles/hot_path_c3_128k_counters.md): FETCH_SIZE 131260.0 and WRITE_SIZE 4095.0 KiB-units per
 # dispatch, scaled by what the same counters read for a 256 MiB copy (x2.0 and x1.0).
 PMC_TRAFFIC_BYTES = {3: int((131260.0 * 2.0 + 4095.0 * 1.0) * 1024)}
 MFMA_BF16_PEAK_TFLOPS = 2500.0   # dense bf16
