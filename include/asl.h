@@ -201,8 +201,8 @@ asl_status asl_join(asl_ctx* ctx, void* stream);
 /* Measurement aid (not a step of the paper's method; for callers that time the kernels of the
  * calls above).  Kernel ids: 0 score row statistics (pass 1), 1 its combine, 2 score column sums
  * (pass 2), 3 pool, 4 sort histogram, 5 sort scatter, 6 rank-variance finalisation (or the
- * below-L_min skip), 7 rank-variance partial sums, 8 select histogram, 9 unused, 10 select write,
- * 11 gather, 12 plain-FMA score kernels.
+ * below-L_min skip), 7 rank-variance partial sums, 8 select histogram, 9 select write, 10 gather,
+ * 11 plain-FMA score kernels.
  * asl_profile_enable: launches whose id bit is set in kernel_mask are bracketed by HIP events on
  *   the call's stream, up to max_records launches (further ones run unrecorded); mask 0 turns
  *   it off and frees the events.  Allocates host memory and events: not for the hot loop.

@@ -196,8 +196,7 @@ class Asl:
 
 
 KERNEL_NAMES = ["score_rowstats", "score_combine", "score_colsum", "pool", "sort_hist", "sort_scatter",
-                "rankvar_final", "rankvar", "select_hist", "select_count", "select_write", "gather",
-                "score_generic"]
+                "rankvar_final", "rankvar", "select_hist", "select_write", "gather", "score_generic"]
 
 
 # -- helpers for the device-resident structs (plumbing only) ---------------------------------------

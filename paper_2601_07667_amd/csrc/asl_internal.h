@@ -10,7 +10,7 @@ namespace asl {
 // Kernel ids for the optional per-kernel event profiling (asl_profile_enable / asl_profile_collect).
 enum KernelId {
   kKernRowstats = 0, kKernCombine, kKernColsum, kKernPool, kKernSortHist, kKernSortScatter,
-  kKernRankvarFinal, kKernRankvar, kKernSelHist, kKernUnused9, kKernSelWrite, kKernGather,
+  kKernRankvarFinal, kKernRankvar, kKernSelHist, kKernSelWrite, kKernGather,
   kKernScoreGeneric, kKernCount
 };
 
