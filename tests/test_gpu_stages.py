@@ -178,6 +178,29 @@ def test_select_random_with_ties(ctx, gpu_device, rows, T, budget, W):
     _select_case(ctx, gpu_device, s, budget, W)
 
 
+def test_rank_select_pool_random_shapes(ctx, gpu_device):
+    """Forty seeded random cases: sizes, budgets, window widths, tie densities and value ranges drawn at
+    random (positive-only scores, mixed signs, a few distinct values, tiny magnitudes)."""
+    rng = np.random.default_rng(20260127)
+    for case in range(40):
+        T = int(rng.integers(1, 9000))
+        rows = int(rng.integers(1, 4))
+        W = int(rng.integers(1, 40))
+        budget = W + int(rng.integers(1, T + 20))
+        kind = case % 4
+        if kind == 0:
+            s = rng.random((rows, T)).astype(np.float32)                          # positive, few ties
+        elif kind == 1:
+            s = np.round(rng.standard_normal((rows, T)), 1).astype(np.float32)     # mixed signs, heavy ties
+        elif kind == 2:
+            s = rng.integers(0, 3, (rows, T)).astype(np.float32)                   # three distinct values
+        else:
+            s = (rng.random((rows, T)) * 1e-30).astype(np.float32)                 # tiny magnitudes / denormals
+        print(f"case {case}: T={T} rows={rows} W={W} budget={budget} kind={kind}", flush=True)
+        _rank_case(ctx, gpu_device, s[0])
+        _select_case(ctx, gpu_device, s, budget, W)
+
+
 def test_select_special(ctx, gpu_device):
     T, W = 6000, 16
     _select_case(ctx, gpu_device, np.ones((2, T), dtype=np.float32), 100, W)               # all equal: first k
