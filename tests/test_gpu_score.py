@@ -75,6 +75,26 @@ def test_other_head_dims_take_the_plain_kernels(gpu_device, d, dtype):
     _compare(gpu_device, _small(4, 2, d, 700, 8, dtype=dtype, seed=d))
 
 
+def test_random_shapes(gpu_device):
+    """Sixteen seeded random shapes: group sizes 1-8, windows 1-64 (M = G*W up to 256, so both the
+    one-block and the two-block wavefront layouts and every wavefront count occur), d in {64, 128},
+    sequence lengths that are not multiples of anything, pooling kernels 1-15."""
+    rng = np.random.default_rng(20260128)
+    done = 0
+    while done < 16:
+        G = int(rng.integers(1, 9))
+        W = int(rng.integers(1, 65))
+        if G * W > 256:
+            continue
+        Hk = int(rng.integers(1, 4))
+        d = int(rng.choice([64, 128]))
+        N = W + int(rng.integers(1, 3000))
+        S = int(rng.choice([1, 3, 7, 15]))
+        print(f"case {done}: Hq={G * Hk} Hk={Hk} d={d} N={N} W={W} S={S} (M={G * W})", flush=True)
+        _compare(gpu_device, _small(G * Hk, Hk, d, N, W, S=S, seed=1000 + done), use_lse=bool(done % 2))
+        done += 1
+
+
 def test_lse_supplied_mode_and_scale(gpu_device):
     L = _small(8, 2, 128, 5000, 32, seed=3)
     P1, s1 = _compare(gpu_device, L)
