@@ -7,8 +7,8 @@
  * KV budget, W, L_min, L_obs, tau, rank cache, init_var).
  *
  * Conventions for every entry point
- *  - Pointers named q_obs, k, v, lse, u, p_head, s_all, scores, rank*, idx*, state, out are
- *    DEVICE pointers owned by the caller.  `params` and `ctx` are HOST pointers.  The library
+ *  - Pointers named q_obs, k, v, lse*, u, p_head, s_all, scores, rank*, idx*, *_ptrs, state, out
+ *    are DEVICE pointers owned by the caller.  `params` and `ctx` are HOST pointers.  The library
  *    owns only the workspace inside asl_ctx (allocated by asl_create; no allocation afterwards).
  *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls enqueue work
  *    and return; they never synchronise.  Calls sharing a ctx share its workspace: calls of the
@@ -111,11 +111,23 @@ size_t asl_workspace_bytes(int32_t max_seq_len, int32_t max_kv_heads, int32_t ma
  *   s_all  [T]     f32 out: sum of P over the KV heads (the vector that is ranked).
  * Logits are scaled q.k with the causal mask on the last W x W block; softmax over all N keys;
  * column sums over the W rows and the G heads of a group, past columns only; AvgPool1D(S,
- * stride 1, zero pad floor(S/2), divisor S).  bf16 inputs use bf16 MFMA with fp32 accumulation;
- * softmax and sums are fp32 and deterministic (fixed reduction order, no float atomics). */
+ * stride 1, zero pad floor(S/2), divisor S).  bf16 inputs with d in {64, 128} and G*W <= 512 use
+ * bf16 MFMA with fp32 accumulation; other shapes take plain fp32-FMA kernels, which are meant for
+ * small problems (ASL_EUNSUPPORTED when Hq*W*N*d exceeds 6e11).  Softmax and sums are fp32 and
+ * deterministic (fixed reduction order, no float atomics). */
 asl_status asl_score_layer(asl_ctx* ctx, const asl_params* params, const void* q_obs,
                            const void* k, const float* lse, float* p_head, float* s_all,
                            void* stream);
+
+/* The normaliser of Alg. 1 step 5's softmax on its own: lse_out[h, i] = natural-log-sum-exp over
+ * all N keys of window row i of query head h's scaled, causally masked logits (the first of
+ * asl_score_layer's two passes over K; fp32, deterministic).
+ *   q_obs, k as in asl_score_layer;  lse_out [Hq, W] f32 out.
+ * Handing lse_out back to asl_score_layer as `lse` gives bit-identical scores to the self-contained
+ * call.  For callers that score one K against the same window more than once, and as the reference
+ * for an attention kernel that produces these values itself. */
+asl_status asl_window_lse(asl_ctx* ctx, const asl_params* params, const void* q_obs, const void* k,
+                          float* lse_out, void* stream);
 
 /* Alg. 1 step 7 on its own: zero-padded moving average, kernel S (odd), stride 1, along T.
  *   u [rows, T] f32 in; p_out [rows, T] f32 out; s_out [T] f32 out or NULL (sum of the pooled rows). */
@@ -140,10 +152,12 @@ asl_status asl_rankvar(asl_ctx* ctx, const int32_t* rank_ring, int32_t l_obs, in
                        int32_t layer_idx, int32_t l_min, int32_t k, double tau,
                        asl_state* state, asl_stat* out, void* stream);
 
-/* Alg. 1 step 11 + Alg. 2: rank s_all into ring row layer_idx % l_obs (a layer index whose ring
- * row is not the one after state->last_layer's restarts the ring; zero the state to start a new
- * sequence), then the statistic as asl_rankvar with
- * k = min(budget - W, T).  The host reads *out after synchronising the stream. */
+/* Alg. 1 step 11 + Alg. 2: rank s_all into ring row layer_idx % l_obs, then the statistic as
+ * asl_rankvar with k = min(budget - W, T).  The host reads *out after synchronising the stream.
+ * The new row continues the rows already held iff layer_idx == state->last_layer + 1, or
+ * layer_idx == state->last_layer + 1 - l_obs (the replay of a captured sequence of l_obs layers,
+ * which overwrites the same ring rows in the same order); any other layer index restarts the ring
+ * from this one row.  Zero the state to start a new sequence. */
 asl_status asl_rank_stat(asl_ctx* ctx, const asl_params* params, const float* s_all,
                          int32_t layer_idx, int32_t l_min, int32_t l_obs, double tau,
                          int32_t* rank_ring, asl_state* state, asl_stat* out, void* stream);
@@ -162,6 +176,19 @@ asl_status asl_select_topk(asl_ctx* ctx, const asl_params* params, const float* 
 asl_status asl_gather_kv(asl_ctx* ctx, const asl_params* params, const void* k, const void* v,
                          const int32_t* idx, int32_t idx_rows, int32_t n_idx, void* k_out,
                          void* v_out, void* stream);
+
+/* Alg. 1 step 12 for many layers in one launch (Sec. 4.2 "Decoding": every layer before the
+ * selection layer keeps a compressed KV cache, each layer's cache being its own allocation).
+ *   k_ptrs, v_ptrs         DEVICE arrays of n_layers device pointers, layer l's K (V) [Hk, N, d]
+ *                          with the strides in params (the same for every layer); 16-byte aligned.
+ *   idx                    [n_layers, idx_rows, n_idx] int32, idx_rows in {1, Hk}, entries in [0, N).
+ *   k_out_ptrs, v_out_ptrs DEVICE arrays of n_layers device pointers to dense [Hk, n_idx, d] outputs.
+ * v_ptrs / v_out_ptrs may both be NULL.  The pointer arrays are read by the kernel only: nothing
+ * is copied or allocated by the call (capturable in a HIP graph).  n_layers <= 16384. */
+asl_status asl_gather_kv_layers(asl_ctx* ctx, const asl_params* params, const void* const* k_ptrs,
+                                const void* const* v_ptrs, const int32_t* idx, int32_t idx_rows,
+                                int32_t n_idx, int32_t n_layers, void* const* k_out_ptrs,
+                                void* const* v_out_ptrs, void* stream);
 
 /* Token propagation at the selection layer (Sec. 4.2 "Prefilling": only the selected tokens go on
  * to the deeper layers; Alg. 2's select_idx applied to the hidden states): dst[i,:] = src[idx[i],:].

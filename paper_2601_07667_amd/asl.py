@@ -20,7 +20,7 @@ ASL_FLAG_DEFER_JOIN = 2
 _STATUS = {0: "ASL_OK", -1: "ASL_EINVAL", -2: "ASL_ENOMEM", -3: "ASL_EHIP", -4: "ASL_EUNSUPPORTED"}
 
 EXPORTS = ["asl_create", "asl_destroy", "asl_last_error", "asl_workspace_bytes", "asl_score_layer",
-           "asl_pool", "asl_rank", "asl_rankvar", "asl_rank_stat", "asl_select_topk", "asl_gather_kv",
+           "asl_window_lse", "asl_gather_kv_layers", "asl_pool", "asl_rank", "asl_rankvar", "asl_rank_stat", "asl_select_topk", "asl_gather_kv",
            "asl_gather_rows", "asl_layer_step", "asl_join", "asl_profile_enable", "asl_profile_collect"]
 
 
@@ -72,6 +72,10 @@ def load() -> C.CDLL:
     lib.asl_workspace_bytes.restype = C.c_size_t
     lib.asl_score_layer.argtypes = [vp, C.POINTER(AslParams), vp, vp, vp, vp, vp, vp]
     lib.asl_score_layer.restype = C.c_int
+    lib.asl_window_lse.argtypes = [vp, C.POINTER(AslParams), vp, vp, vp, vp]
+    lib.asl_window_lse.restype = C.c_int
+    lib.asl_gather_kv_layers.argtypes = [vp, C.POINTER(AslParams), vp, vp, vp, i32, i32, i32, vp, vp, vp]
+    lib.asl_gather_kv_layers.restype = C.c_int
     lib.asl_pool.argtypes = [vp, vp, i32, i32, i32, vp, vp, vp]
     lib.asl_pool.restype = C.c_int
     lib.asl_rank.argtypes = [vp, vp, i32, vp, vp]
@@ -146,6 +150,17 @@ class Asl:
     def asl_score_layer(self, params: AslParams, q_obs, k, p_head, s_all, lse=None) -> None:
         self._check(self.lib.asl_score_layer(self.h, C.byref(params), _ptr(q_obs), _ptr(k), _ptr(lse),
                                              _ptr(p_head), _ptr(s_all), _stream()))
+
+    def asl_window_lse(self, params: AslParams, q_obs, k, lse_out) -> None:
+        self._check(self.lib.asl_window_lse(self.h, C.byref(params), _ptr(q_obs), _ptr(k), _ptr(lse_out),
+                                            _stream()))
+
+    def asl_gather_kv_layers(self, params: AslParams, k_ptrs, v_ptrs, idx, idx_rows: int, n_idx: int,
+                             n_layers: int, k_out_ptrs, v_out_ptrs) -> None:
+        """k_ptrs .. v_out_ptrs: int64 device tensors holding one device pointer per layer."""
+        self._check(self.lib.asl_gather_kv_layers(self.h, C.byref(params), _ptr(k_ptrs), _ptr(v_ptrs), _ptr(idx),
+                                                  idx_rows, n_idx, n_layers, _ptr(k_out_ptrs), _ptr(v_out_ptrs),
+                                                  _stream()))
 
     def asl_pool(self, u, rows: int, T: int, S: int, p_out, s_out=None) -> None:
         self._check(self.lib.asl_pool(self.h, _ptr(u), rows, T, S, _ptr(p_out), _ptr(s_out), _stream()))

@@ -269,13 +269,8 @@ asl_status asl_destroy(asl_ctx* ctx) {
 
 const char* asl_last_error(const asl_ctx* ctx) { return ctx ? ctx->err : "null context"; }
 
-// Scoring + pooling.  With wait_side set, the pooling kernel (the first one that overwrites the
-// score rows) is ordered behind the side-stream work a deferred asl_layer_step left behind.
-static asl_status score_layer_impl(asl_ctx* ctx, const asl_params* p, const void* q_obs, const void* k,
-                                   const float* lse, float* p_head, float* s_all, void* stream, bool wait_side) {
-  asl_status st = check_params(ctx, p);
-  if (st != ASL_OK) return st;
-  if (!q_obs || !k || !p_head || !s_all) return fail(ctx, ASL_EINVAL, "null tensor pointer");
+// Stride and alignment rules of the scoring kernels' operands.
+static asl_status check_score_operands(asl_ctx* ctx, const asl_params* p, const void* q_obs, const void* k) {
   if (p->k_stride_tok < p->head_dim || p->k_stride_head < 0)
     return fail(ctx, ASL_EINVAL, "k strides must satisfy stride_tok >= d, stride_head >= 0");
   const int eb = elem_bytes(p->dtype);
@@ -283,10 +278,30 @@ static asl_status score_layer_impl(asl_ctx* ctx, const asl_params* p, const void
       (!aligned16(q_obs) || !aligned16(k) || (p->k_stride_tok * eb) % 16 != 0 ||
        (p->k_stride_head * eb) % 16 != 0))
     return fail(ctx, ASL_EUNSUPPORTED, "q_obs/k must be 16-byte aligned with 16-byte-multiple strides");
+  // the plain-FMA kernels walk every key with one thread per query row or per key: refuse the sizes
+  // at which that would take seconds rather than hand back a call that looks hung
+  if (!asl::score_mfma_supported(*p) || (p->flags & ASL_FLAG_GENERIC_SCORE)) {
+    const double work = (double)p->n_q_heads * p->window * (double)p->seq_len * p->head_dim;
+    if (work > 6.0e11)
+      return fail(ctx, ASL_EUNSUPPORTED,
+                  "this shape (dtype/head_dim/G*W) has no MFMA scoring kernel and is too large for the plain one");
+  }
+  return ASL_OK;
+}
+
+// Scoring + pooling.  With wait_side set, the pooling kernel (the first one that overwrites the
+// score rows) is ordered behind the side-stream work a deferred asl_layer_step left behind.
+static asl_status score_layer_impl(asl_ctx* ctx, const asl_params* p, const void* q_obs, const void* k,
+                                   const float* lse, float* p_head, float* s_all, void* stream, bool wait_side) {
+  asl_status st = check_params(ctx, p);
+  if (st != ASL_OK) return st;
+  if (!q_obs || !k || !p_head || !s_all) return fail(ctx, ASL_EINVAL, "null tensor pointer");
+  st = check_score_operands(ctx, p, q_obs, k);
+  if (st != ASL_OK) return st;
   DeviceGuard guard(ctx->device);
   if (guard.err != hipSuccess) return hip_fail(ctx, guard.err, "set device");
   hipStream_t hs = static_cast<hipStream_t>(stream);
-  hipError_t e = asl::launch_score(*p, ctx->ws, q_obs, k, lse, hs);
+  hipError_t e = asl::launch_score(*p, ctx->ws, q_obs, k, lse, nullptr, hs);
   if (e != hipSuccess) return hip_fail(ctx, e, "score launch");
   if (wait_side && ctx->side_pending) {
     e = hipStreamWaitEvent(hs, ctx->ev_join, 0);
@@ -302,6 +317,20 @@ static asl_status score_layer_impl(asl_ctx* ctx, const asl_params* p, const void
 asl_status asl_score_layer(asl_ctx* ctx, const asl_params* p, const void* q_obs, const void* k,
                            const float* lse, float* p_head, float* s_all, void* stream) {
   return score_layer_impl(ctx, p, q_obs, k, lse, p_head, s_all, stream, false);
+}
+
+asl_status asl_window_lse(asl_ctx* ctx, const asl_params* p, const void* q_obs, const void* k,
+                          float* lse_out, void* stream) {
+  asl_status st = check_params(ctx, p);
+  if (st != ASL_OK) return st;
+  if (!q_obs || !k || !lse_out) return fail(ctx, ASL_EINVAL, "null tensor pointer");
+  st = check_score_operands(ctx, p, q_obs, k);
+  if (st != ASL_OK) return st;
+  DeviceGuard guard(ctx->device);
+  if (guard.err != hipSuccess) return hip_fail(ctx, guard.err, "set device");
+  hipError_t e = asl::launch_score(*p, ctx->ws, q_obs, k, nullptr, lse_out, static_cast<hipStream_t>(stream));
+  if (e != hipSuccess) return hip_fail(ctx, e, "score launch");
+  return ASL_OK;
 }
 
 asl_status asl_pool(asl_ctx* ctx, const float* u, int32_t rows, int32_t T, int32_t S, float* p_out,
@@ -419,9 +448,64 @@ asl_status asl_gather_kv(asl_ctx* ctx, const asl_params* p, const void* k, const
     return fail(ctx, ASL_EINVAL, "token stride smaller than head_dim");
   DeviceGuard guard(ctx->device);
   if (guard.err != hipSuccess) return hip_fail(ctx, guard.err, "set device");
-  hipError_t e = asl::launch_gather(ctx->ws.prof, k, v, idx, idx_rows, n_idx, p->n_kv_heads, (int)row_bytes,
-                                    p->k_stride_head * eb, p->k_stride_tok * eb, p->v_stride_head * eb,
-                                    p->v_stride_tok * eb, k_out, v_out, static_cast<hipStream_t>(stream));
+  asl::GatherArgs ga = {};
+  ga.k = static_cast<const char*>(k);
+  ga.v = static_cast<const char*>(v);
+  ga.k_out = static_cast<char*>(k_out);
+  ga.v_out = static_cast<char*>(v_out);
+  ga.idx = idx;
+  ga.ksh = p->k_stride_head * eb;
+  ga.kst = p->k_stride_tok * eb;
+  ga.vsh = p->v_stride_head * eb;
+  ga.vst = p->v_stride_tok * eb;
+  ga.idx_rows = idx_rows;
+  ga.n_idx = n_idx;
+  ga.cpr = (int)(row_bytes / 16);
+  ga.n_tensors = v ? 2 : 1;
+  hipError_t e = asl::launch_gather(ctx->ws.prof, ga, p->n_kv_heads, 1, static_cast<hipStream_t>(stream));
+  if (e != hipSuccess) return hip_fail(ctx, e, "gather launch");
+  return ASL_OK;
+}
+
+asl_status asl_gather_kv_layers(asl_ctx* ctx, const asl_params* p, const void* const* k_ptrs,
+                                const void* const* v_ptrs, const int32_t* idx, int32_t idx_rows,
+                                int32_t n_idx, int32_t n_layers, void* const* k_out_ptrs,
+                                void* const* v_out_ptrs, void* stream) {
+  asl_status st = check_params(ctx, p);
+  if (st != ASL_OK) return st;
+  if (!k_ptrs || !idx || !k_out_ptrs) return fail(ctx, ASL_EINVAL, "null pointer");
+  if ((v_ptrs == nullptr) != (v_out_ptrs == nullptr))
+    return fail(ctx, ASL_EINVAL, "v_ptrs and v_out_ptrs must both be given or both be null");
+  if (idx_rows != 1 && idx_rows != p->n_kv_heads)
+    return fail(ctx, ASL_EINVAL, "idx_rows must be 1 or Hk (got %d)", idx_rows);
+  if (n_idx < 0 || n_layers < 0) return fail(ctx, ASL_EINVAL, "n_idx and n_layers must be >= 0");
+  if (n_layers > 16384) return fail(ctx, ASL_EUNSUPPORTED, "more than 16384 layers per call");
+  const int eb = elem_bytes(p->dtype);
+  const int64_t row_bytes = (int64_t)p->head_dim * eb;
+  // the per-layer pointers live in device memory and are not inspected here: their 16-byte
+  // alignment is the caller's contract
+  if (row_bytes % 16 != 0 || (p->k_stride_tok * eb) % 16 != 0 || (p->k_stride_head * eb) % 16 != 0 ||
+      (v_ptrs && ((p->v_stride_tok * eb) % 16 != 0 || (p->v_stride_head * eb) % 16 != 0)))
+    return fail(ctx, ASL_EUNSUPPORTED, "gather needs 16-byte aligned rows and strides");
+  if (p->k_stride_tok < p->head_dim || (v_ptrs && p->v_stride_tok < p->head_dim))
+    return fail(ctx, ASL_EINVAL, "token stride smaller than head_dim");
+  DeviceGuard guard(ctx->device);
+  if (guard.err != hipSuccess) return hip_fail(ctx, guard.err, "set device");
+  asl::GatherArgs ga = {};
+  ga.k_ptrs = k_ptrs;
+  ga.v_ptrs = v_ptrs;
+  ga.k_out_ptrs = k_out_ptrs;
+  ga.v_out_ptrs = v_out_ptrs;
+  ga.idx = idx;
+  ga.ksh = p->k_stride_head * eb;
+  ga.kst = p->k_stride_tok * eb;
+  ga.vsh = p->v_stride_head * eb;
+  ga.vst = p->v_stride_tok * eb;
+  ga.idx_rows = idx_rows;
+  ga.n_idx = n_idx;
+  ga.cpr = (int)(row_bytes / 16);
+  ga.n_tensors = v_ptrs ? 2 : 1;
+  hipError_t e = asl::launch_gather(ctx->ws.prof, ga, p->n_kv_heads, n_layers, static_cast<hipStream_t>(stream));
   if (e != hipSuccess) return hip_fail(ctx, e, "gather launch");
   return ASL_OK;
 }
@@ -436,8 +520,16 @@ asl_status asl_gather_rows(asl_ctx* ctx, const void* src, int64_t src_row_stride
     return fail(ctx, ASL_EUNSUPPORTED, "gather needs 16-byte aligned rows, pointers and strides");
   DeviceGuard guard(ctx->device);
   if (guard.err != hipSuccess) return hip_fail(ctx, guard.err, "set device");
-  hipError_t e = asl::launch_gather(ctx->ws.prof, src, nullptr, idx, 1, n_idx, 1, row_bytes, 0,
-                                    src_row_stride_bytes, 0, 0, dst, nullptr, static_cast<hipStream_t>(stream));
+  asl::GatherArgs ga = {};
+  ga.k = static_cast<const char*>(src);
+  ga.k_out = static_cast<char*>(dst);
+  ga.idx = idx;
+  ga.kst = src_row_stride_bytes;
+  ga.idx_rows = 1;
+  ga.n_idx = n_idx;
+  ga.cpr = row_bytes / 16;
+  ga.n_tensors = 1;
+  hipError_t e = asl::launch_gather(ctx->ws.prof, ga, 1, 1, static_cast<hipStream_t>(stream));
   if (e != hipSuccess) return hip_fail(ctx, e, "gather launch");
   return ASL_OK;
 }

@@ -101,7 +101,7 @@ __device__ __forceinline__ uint32_t hist_total(const uint32_t* h, int digit) {
 #endif
 
 hipError_t launch_score(const asl_params& p, const Workspace& ws, const void* q_obs, const void* k,
-                        const float* lse, hipStream_t st);
+                        const float* lse, float* lse_out, hipStream_t st);
 hipError_t launch_pool(Prof* prof, const float* u, int rows, int T, int S, float* p_out, float* s_out,
                        hipStream_t st);
 hipError_t launch_rank(const Workspace& ws, const float* s, int T, int32_t* rank_out, hipStream_t st);
@@ -113,12 +113,27 @@ hipError_t launch_stat_skip(Prof* prof, asl_stat* out, asl_state* state, int lay
                             int push, hipStream_t st);
 hipError_t launch_select(const Workspace& ws, const float* scores, int rows, int T, int k, int W,
                          int32_t* idx_out, hipStream_t st);
-hipError_t launch_gather(Prof* prof, const void* k, const void* v, const int32_t* idx, int idx_rows, int n_idx,
-                         int Hk, int row_bytes, int64_t k_stride_head_b, int64_t k_stride_tok_b,
-                         int64_t v_stride_head_b, int64_t v_stride_tok_b, void* k_out, void* v_out,
-                         hipStream_t st);
+// Arguments of the row-gather kernel.  Either k/v/k_out/v_out name one layer's tensors, or the
+// *_ptrs members name device arrays with one pointer per layer (then k..v_out are unused).
+struct GatherArgs {
+  const char* k;
+  const char* v;                 // null when n_tensors == 1
+  char* k_out;
+  char* v_out;
+  const void* const* k_ptrs;     // device arrays [n_layers], or null
+  const void* const* v_ptrs;
+  void* const* k_out_ptrs;
+  void* const* v_out_ptrs;
+  const int32_t* idx;            // [n_layers][idx_rows][n_idx]
+  int64_t ksh, kst, vsh, vst;    // head / token strides in bytes
+  int idx_rows;                  // 1 (shared by the heads) or Hk
+  int n_idx;
+  int cpr;                       // 16-byte pieces per row
+  int cpr_shift;                 // log2(cpr) when cpr is a power of two (set by launch_gather)
+  int n_tensors;                 // 1 (K only) or 2 (K and V)
+};
+hipError_t launch_gather(Prof* prof, const GatherArgs& args, int Hk, int n_layers, hipStream_t st);
 
 bool score_mfma_supported(const asl_params& p);
-int score_chunks(const asl_params& p);
 
 }  // namespace asl

@@ -13,11 +13,19 @@ namespace asl {
 
 constexpr int kVarThreads = 256;
 
+// The ring row of layer_idx continues the rows already held iff layer_idx is the layer after
+// state->last_layer, or that layer minus l_obs (a captured trip of l_obs layers round the ring being
+// replayed: the same rows are overwritten in the same order).  Any other index restarts the ring.
+__device__ __forceinline__ bool continues_ring(const asl_state* state, int layer_idx, int l_obs) {
+  const int next = state->last_layer + 1;
+  return layer_idx == next || layer_idx == next - l_obs;
+}
+
 __global__ void stat_skip_kernel(asl_stat* out, asl_state* state, int layer_idx, int l_obs, int push) {
   if (threadIdx.x != 0 || blockIdx.x != 0) return;
   if (push) {
     int n = state->n_valid_rows;
-    if (n > 0 && (state->last_layer + 1) % l_obs != layer_idx % l_obs) n = 0;   // not the next ring row
+    if (n > 0 && !continues_ring(state, layer_idx, l_obs)) n = 0;
     state->n_valid_rows = n + 1 < l_obs ? n + 1 : l_obs;
     state->last_layer = layer_idx;
   }
@@ -35,7 +43,7 @@ __global__ void stat_skip_kernel(asl_stat* out, asl_state* state, int layer_idx,
 __device__ __forceinline__ int rows_in_use(const asl_state* state, int layer_idx, int l_obs, int push) {
   int n = state->n_valid_rows;
   if (push) {
-    if (n > 0 && (state->last_layer + 1) % l_obs != layer_idx % l_obs) n = 0;   // not the next ring row
+    if (n > 0 && !continues_ring(state, layer_idx, l_obs)) n = 0;
     n = n + 1 < l_obs ? n + 1 : l_obs;
   }
   return n;

@@ -14,8 +14,6 @@
 // (v_mfma_f32_32x32x16_bf16), each fragment once for all its row blocks.  Pass 1 puts keys on the
 // accumulator's register axis (row statistics reduce in-lane), pass 2 puts query rows there
 // (column sums reduce in-lane).  All reductions have a fixed order: results are deterministic.
-#include <cstdlib>
-
 #include "asl_internal.h"
 
 namespace asl {
@@ -38,13 +36,10 @@ constexpr int KT = ASL_SCORE_KT;              // keys per LDS tile (a multiple o
 // (two larger workgroups per compute unit, hence a deeper ring each).
 template <int RB> constexpr int ring_stages() { return RB > 1 ? ASL_SCORE_STAGES_RB2 : ASL_SCORE_STAGES; }
 constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
 constexpr float kNegBig = -1.0e30f;           // finite stand-in for "no maximum yet"
 
-#ifdef ASL_DIAG_NOEXP   // diagnosis builds only: wrong results, shows how much time the exponentials cost
-__device__ __forceinline__ float fast_exp2(float x) { return x; }
-#else
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
-#endif
 
 // Row of the 32x32 accumulator held by register r of a lane in half `half` (lanes 32..63 = 1).
 __device__ __forceinline__ int acc_row(int r, int half) { return 8 * (r >> 2) + 4 * half + (r & 3); }
@@ -57,11 +52,16 @@ __device__ __forceinline__ int acc_row(int r, int half) { return 8 * (r >> 2) + 
 // Rows past N are clamped to the last key (they are masked or discarded later).
 // Per-thread constants of the tile loader: for each of its NLOAD pieces the tile row and the byte
 // offset of the (swizzled) source piece from the tile's first key.
+// The first NT threads of the workgroup do the loading, NT = the largest power of two that is at most
+// the workgroup size and the number of pieces (see loader_threads): every loading wavefront then
+// issues the same number of loads per tile, which the counted waits below rely on; the other
+// wavefronts issue none and are held by the workgroup barrier alone.
 template <int D, int NT>
 struct TilePieces {
   static constexpr int CPR = D / 8;                   // 16-byte pieces per key row
   static constexpr int SLOTS = KT * CPR;
-  static constexpr int NLOAD = (SLOTS + NT - 1) / NT;
+  static_assert(SLOTS % NT == 0, "loader threads must divide the pieces of a tile");
+  static constexpr int NLOAD = SLOTS / NT;
   uint32_t src_off[NLOAD];
   int row[NLOAD];
   int col8[NLOAD];
@@ -81,13 +81,13 @@ template <int D, int NT, bool FULL>
 __device__ __forceinline__ void issue_tile_loads_impl(const TilePieces<D, NT>& tp,
                                                       const __bf16* __restrict__ kg, int64_t kst, int key0,
                                                       int N, __bf16* __restrict__ lds_buf, int tid) {
-  constexpr int SLOTS = TilePieces<D, NT>::SLOTS;
   constexpr int NLOAD = TilePieces<D, NT>::NLOAD;
   const int wave_slot0 = __builtin_amdgcn_readfirstlane(tid) & ~63;
+  if (wave_slot0 >= NT) return;                         // not a loading wavefront (wave-uniform)
   const char* tile_base = reinterpret_cast<const char*>(kg + (int64_t)key0 * kst);   // uniform
 #pragma unroll
   for (int i = 0; i < NLOAD; ++i) {
-    if (SLOTS % NT == 0 || i * NT + tid < SLOTS) {
+    {
       const char* src;
       if (FULL) {
         src = tile_base + tp.src_off[i];
@@ -122,9 +122,17 @@ __device__ __forceinline__ void wait_vmem() {
   __builtin_amdgcn_s_waitcnt(0x0F70 | (CNT & 0xF) | ((CNT >> 4) << 14));
 }
 
-// Loads each wave issues per tile, when that number is the same for every wave (else -1).
+// Threads of an NW-wavefront workgroup that load the K tiles.
+template <int D, int NW>
+constexpr int loader_threads() {
+  int n = 64;
+  while (n * 2 <= NW * 64 && n * 2 <= KT * (D / 8)) n *= 2;
+  return n;
+}
+
+// Loads each loading wave issues per tile.
 template <int D, int NT>
-constexpr int tile_loads_per_wave() { return ((KT * (D / 8)) % NT == 0) ? (KT * (D / 8)) / NT : -1; }
+constexpr int tile_loads_per_wave() { return (KT * (D / 8)) / NT; }
 
 // Top-of-iteration wait: the current tile must have landed.  `younger` = tiles issued after it that
 // are still in flight (at most STAGES-2).  With a uniform per-wave load count those may stay
@@ -164,11 +172,7 @@ __device__ __forceinline__ void mma_subtile(const __bf16* __restrict__ buf, int 
     for (int r = 0; r < 16; ++r) acc[rb][r] = 0.f;
 #pragma unroll
   for (int ks = 0; ks < D / 16; ++ks) {
-#ifdef ASL_DIAG_ONEFRAG   // diagnosis builds only: wrong results, one LDS fragment read per sub-tile
-    const bf16x8 kf = load_k_frag<D>(buf, sub, ln, half, 0);
-#else
     const bf16x8 kf = load_k_frag<D>(buf, sub, ln, half, ks);
-#endif
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb)
       acc[rb] = KEYS_ON_REGS ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[rb][ks], acc[rb], 0, 0, 0)
@@ -301,7 +305,7 @@ __global__ void __launch_bounds__(NW * 64)
 score_rowstats_kernel(const __bf16* __restrict__ q_obs, const __bf16* __restrict__ k, int64_t ksh,
                       int64_t kst, int Hk, int M, int W, int N, int n_cu, int n_chunks,
                       float c1, float* __restrict__ row_part) {
-  constexpr int NT = NW * 64;
+  constexpr int NT = loader_threads<D, NW>();      // threads that load the K tiles
   constexpr int KS = D / 16;
   constexpr int TILE_ELEMS = KT * D;
   constexpr int STAGES = ring_stages<RB>();
@@ -360,9 +364,10 @@ score_rowstats_kernel(const __bf16* __restrict__ q_obs, const __bf16* __restrict
 
 // Fold the per-chunk partials of every row into one log2-domain offset  m + log2(Z).
 // One wavefront per row: lanes stride over the chunks, then a fixed-order butterfly.
+// lse_out (optional): the same quantity as a natural logarithm, the rows' log-sum-exp.
 __global__ void __launch_bounds__(256)
 score_combine_kernel(const float* __restrict__ row_part, int Hk, int M, int n_chunks,
-                     float* __restrict__ row_const) {
+                     float* __restrict__ row_const, float* __restrict__ lse_out) {
   const int lane = threadIdx.x & 63;
   const int r = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (r >= Hk * M) return;
@@ -384,7 +389,11 @@ score_combine_kernel(const float* __restrict__ row_part, int Hk, int M, int n_ch
     z = (lane & o) ? (zb + za) : (za + zb);
     m = mn;
   }
-  if (lane == 0) row_const[r] = m + log2f(z);
+  if (lane == 0) {
+    const float c = m + log2f(z);
+    row_const[r] = c;
+    if (lse_out != nullptr) lse_out[r] = c * kLn2;
+  }
 }
 
 // One tile of pass 2: start the next tile's loads into `nxt`, then the column partial sums of
@@ -427,7 +436,8 @@ __global__ void __launch_bounds__(NW * 64)
 score_colsum_kernel(const __bf16* __restrict__ q_obs, const __bf16* __restrict__ k, int64_t ksh,
                     int64_t kst, int Hk, int M, int N, int T, int n_cu, float c1,
                     const float* __restrict__ row_const, float rc_mul, float* __restrict__ u_group) {
-  constexpr int NT = NW * 64;
+  constexpr int NT = loader_threads<D, NW>();      // threads that load the K tiles
+  constexpr int NTHREADS = NW * 64;
   constexpr int KS = D / 16;
   constexpr int TILE_ELEMS = KT * D;
   constexpr int STAGES = ring_stages<RB>();
@@ -463,7 +473,7 @@ score_colsum_kernel(const __bf16* __restrict__ q_obs, const __bf16* __restrict__
 
   // sum the waves' partials of one finished tile in a fixed order and store the past columns
   auto reduce_store = [&](int buf_idx, int kbase) {
-    for (int j = tid; j < KT; j += NT) {
+    for (int j = tid; j < KT; j += NTHREADS) {
       float s = red[buf_idx][0][j];
 #pragma unroll
       for (int w = 1; w < NW; ++w) s += red[buf_idx][w][j];
@@ -500,7 +510,8 @@ template <> __device__ __forceinline__ float ldf<__bf16>(const __bf16* p) { retu
 template <typename TIn>
 __global__ void __launch_bounds__(256)
 score_rowstats_generic(const TIn* __restrict__ q_obs, const TIn* __restrict__ k, int64_t ksh, int64_t kst,
-                       int G, int W, int N, int D, float c1, float* __restrict__ row_const) {
+                       int G, int W, int N, int D, float c1, float* __restrict__ row_const,
+                       float* __restrict__ lse_out) {
   extern __shared__ float sm[];                // D floats of q, then 2*256 for the reduction
   float* qs = sm;
   float* red_m = sm + D;
@@ -533,7 +544,11 @@ score_rowstats_generic(const TIn* __restrict__ q_obs, const TIn* __restrict__ k,
     }
     __syncthreads();
   }
-  if (threadIdx.x == 0) row_const[r] = red_m[0] + log2f(red_z[0]);
+  if (threadIdx.x == 0) {
+    const float c = red_m[0] + log2f(red_z[0]);
+    row_const[r] = c;
+    if (lse_out != nullptr) lse_out[r] = c * kLn2;
+  }
 }
 
 // one thread per (KV head g, past key j): loop over the M rows of the group
@@ -557,32 +572,13 @@ score_colsum_generic(const TIn* __restrict__ q_obs, const TIn* __restrict__ k, i
 }
 
 // ---------------------------------------------------------------------------------------------
+// Largest number of query rows per KV head (G*W) the MFMA kernels take: eight wavefronts of two
+// 32-row blocks.
+constexpr int kMaxMfmaRows = 512;
+
 bool score_mfma_supported(const asl_params& p) {
   const int M = (p.n_q_heads / p.n_kv_heads) * p.window;
-  return p.dtype == ASL_BF16 && (p.head_dim == 64 || p.head_dim == 128) && M <= 256;
-}
-
-// Query-row blocks per wavefront: one up to M = 128 rows per KV head, two above.
-static int score_row_blocks(int M) { return M > 128 ? 2 : 1; }
-
-// Key chunks per KV head: one resident round of workgroups, so that no second, partly filled
-// round trails behind.  Tunable through ASL_SCORE_WORKGROUPS (total workgroups per pass).
-int score_chunks(const asl_params& p) {
-  static const int forced = [] {
-    const char* e = getenv("ASL_SCORE_WORKGROUPS");
-    const int v = e ? atoi(e) : 0;
-    return v > 0 ? v : 0;
-  }();
-  const int M = (p.n_q_heads / p.n_kv_heads) * p.window;
-  // 256 CUs x resident workgroups per CU (three with one row block per wavefront, two with two)
-  const int target = forced ? forced : (score_row_blocks(M) > 1 ? 512 : 768);
-  const int n_tiles = (p.seq_len + KT - 1) / KT;
-  int want = target / p.n_kv_heads;
-  if (want > kMaxChunks) want = kMaxChunks;
-  if (want > n_tiles) want = n_tiles;
-  if (want < 1) want = 1;
-  const int tpc = (n_tiles + want - 1) / want;
-  return (n_tiles + tpc - 1) / tpc;
+  return p.dtype == ASL_BF16 && (p.head_dim == 64 || p.head_dim == 128) && M <= kMaxMfmaRows;
 }
 
 // Compute units of the current device (256 on MI355X).
@@ -597,11 +593,42 @@ static int device_cu_count() {
   return n;
 }
 
+// Key chunks per KV head for a pass whose kernel fits `resident` workgroups per compute unit: one
+// resident round of workgroups, so that no second, partly filled round trails behind.
+static int score_chunks(const asl_params& p, int resident) {
+  const int target = device_cu_count() * resident;
+  const int n_tiles = (p.seq_len + KT - 1) / KT;
+  int want = target / p.n_kv_heads;
+  if (want > kMaxChunks) want = kMaxChunks;
+  if (want > n_tiles) want = n_tiles;
+  if (want < 1) want = 1;
+  const int tpc = (n_tiles + want - 1) / want;
+  return (n_tiles + tpc - 1) / tpc;
+}
+
+// Workgroups of `kernel` that fit on one compute unit at once (registers, LDS, wave slots).
+template <typename K>
+static int resident_per_cu(K kernel, int threads) {
+  int n = 0;
+  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, kernel, threads, 0) != hipSuccess || n < 1) {
+    (void)hipGetLastError();
+    n = 1;
+  }
+  return n;
+}
+
 template <int D, int NW, int RB>
 static hipError_t launch_score_mfma(const asl_params& p, const Workspace& ws, const __bf16* q,
-                                    const __bf16* k, const float* lse, float c1, hipStream_t st) {
+                                    const __bf16* k, const float* lse, float* lse_out, float c1,
+                                    hipStream_t st) {
   const int Hk = p.n_kv_heads, M = (p.n_q_heads / Hk) * p.window, N = p.seq_len, T = N - p.window;
-  const int n_chunks = score_chunks(p);
+  // both passes use the same LDS ring and nearly the same registers; take the smaller residency
+  static const int resident = [] {
+    const int a = resident_per_cu(score_rowstats_kernel<D, NW, RB>, NW * 64);
+    const int b = resident_per_cu(score_colsum_kernel<D, NW, RB>, NW * 64);
+    return a < b ? a : b;
+  }();
+  const int n_chunks = score_chunks(p, resident);
   const int n_cu = device_cu_count();
   if (!lse) {
     ASL_LAUNCH(ws.prof, kKernRowstats, st, (score_rowstats_kernel<D, NW, RB>), dim3(Hk * n_chunks), dim3(NW * 64), 0, st, q, k,
@@ -609,8 +636,9 @@ static hipError_t launch_score_mfma(const asl_params& p, const Workspace& ws, co
                        ws.row_part);
     const int rows = Hk * M;
     ASL_LAUNCH(ws.prof, kKernCombine, st, score_combine_kernel, dim3((rows + 3) / 4), dim3(256), 0, st, ws.row_part,
-                       Hk, M, n_chunks, ws.row_const);
+                       Hk, M, n_chunks, ws.row_const, lse_out);
   }
+  if (lse_out) return hipGetLastError();          // only the row normalisers were asked for
   const int n_tiles2 = (T + KT - 1) / KT;
   const int n_chunks2 = n_chunks < n_tiles2 ? n_chunks : n_tiles2;
   ASL_LAUNCH(ws.prof, kKernColsum, st, (score_colsum_kernel<D, NW, RB>), dim3(Hk * n_chunks2), dim3(NW * 64), 0, st, q, k,
@@ -619,54 +647,65 @@ static hipError_t launch_score_mfma(const asl_params& p, const Workspace& ws, co
   return hipGetLastError();
 }
 
-// M <= 128: wavefronts of one 32-row block, NW = ceil(M / 32); above: two blocks each, NW = ceil(M / 64).
+// Wavefronts and 32-row blocks per wavefront for M query rows per KV head: one block per wavefront
+// up to 128 rows; two above, with ceil(M / 64) wavefronts (up to eight, M <= 512).
 template <int D>
 static hipError_t dispatch_nw(int M, const asl_params& p, const Workspace& ws, const __bf16* q,
-                              const __bf16* k, const float* lse, float c1, hipStream_t st) {
-  if (score_row_blocks(M) == 1) {
+                              const __bf16* k, const float* lse, float* lse_out, float c1, hipStream_t st) {
+  if (M <= 128) {
     switch ((M + 31) / 32) {
-      case 1: return launch_score_mfma<D, 1, 1>(p, ws, q, k, lse, c1, st);
-      case 2: return launch_score_mfma<D, 2, 1>(p, ws, q, k, lse, c1, st);
-      case 3: return launch_score_mfma<D, 3, 1>(p, ws, q, k, lse, c1, st);
-      default: return launch_score_mfma<D, 4, 1>(p, ws, q, k, lse, c1, st);
+      case 1: return launch_score_mfma<D, 1, 1>(p, ws, q, k, lse, lse_out, c1, st);
+      case 2: return launch_score_mfma<D, 2, 1>(p, ws, q, k, lse, lse_out, c1, st);
+      case 3: return launch_score_mfma<D, 3, 1>(p, ws, q, k, lse, lse_out, c1, st);
+      default: return launch_score_mfma<D, 4, 1>(p, ws, q, k, lse, lse_out, c1, st);
     }
   }
-  return (M + 63) / 64 == 3 ? launch_score_mfma<D, 3, 2>(p, ws, q, k, lse, c1, st)
-                            : launch_score_mfma<D, 4, 2>(p, ws, q, k, lse, c1, st);
+  switch ((M + 63) / 64) {
+    case 3: return launch_score_mfma<D, 3, 2>(p, ws, q, k, lse, lse_out, c1, st);
+    case 4: return launch_score_mfma<D, 4, 2>(p, ws, q, k, lse, lse_out, c1, st);
+    case 5: return launch_score_mfma<D, 5, 2>(p, ws, q, k, lse, lse_out, c1, st);
+    case 6: return launch_score_mfma<D, 6, 2>(p, ws, q, k, lse, lse_out, c1, st);
+    case 7: return launch_score_mfma<D, 7, 2>(p, ws, q, k, lse, lse_out, c1, st);
+    default: return launch_score_mfma<D, 8, 2>(p, ws, q, k, lse, lse_out, c1, st);
+  }
 }
 
 template <typename TIn>
 static hipError_t launch_score_generic(const asl_params& p, const Workspace& ws, const TIn* q,
-                                       const TIn* k, const float* lse, float c1, hipStream_t st) {
+                                       const TIn* k, const float* lse, float* lse_out, float c1,
+                                       hipStream_t st) {
   const int Hk = p.n_kv_heads, G = p.n_q_heads / Hk, W = p.window, M = G * W, N = p.seq_len, T = N - W;
   const int D = p.head_dim;
   if (!lse) {
     size_t sm = (size_t)(D + 512) * sizeof(float);
     ASL_LAUNCH(ws.prof, kKernScoreGeneric, st, (score_rowstats_generic<TIn>), dim3(p.n_q_heads * W), dim3(256), sm, st, q, k,
-                       p.k_stride_head, p.k_stride_tok, G, W, N, D, c1, ws.row_const);
+                       p.k_stride_head, p.k_stride_tok, G, W, N, D, c1, ws.row_const, lse_out);
   }
+  if (lse_out) return hipGetLastError();
   ASL_LAUNCH(ws.prof, kKernScoreGeneric, st, (score_colsum_generic<TIn>), dim3((T + 255) / 256, Hk), dim3(256), 0, st, q, k,
                      p.k_stride_head, p.k_stride_tok, M, T, D, c1, lse ? lse : ws.row_const,
                      lse ? kLog2e : 1.0f, ws.u_group);
   return hipGetLastError();
 }
 
+// lse != null: the rows' log-sum-exp is given, only the column-sum pass runs.  lse_out != null (and
+// lse == null): only the row-statistics pass runs and the rows' log-sum-exp is written there.
 hipError_t launch_score(const asl_params& p, const Workspace& ws, const void* q_obs, const void* k,
-                        const float* lse, hipStream_t st) {
+                        const float* lse, float* lse_out, hipStream_t st) {
   const float scale = p.scale > 0.f ? p.scale : 1.0f / sqrtf((float)p.head_dim);
   const float c1 = scale * kLog2e;
   const int M = (p.n_q_heads / p.n_kv_heads) * p.window;
   if (score_mfma_supported(p) && !(p.flags & ASL_FLAG_GENERIC_SCORE)) {
     const __bf16* q = static_cast<const __bf16*>(q_obs);
     const __bf16* kk = static_cast<const __bf16*>(k);
-    return p.head_dim == 128 ? dispatch_nw<128>(M, p, ws, q, kk, lse, c1, st)
-                             : dispatch_nw<64>(M, p, ws, q, kk, lse, c1, st);
+    return p.head_dim == 128 ? dispatch_nw<128>(M, p, ws, q, kk, lse, lse_out, c1, st)
+                             : dispatch_nw<64>(M, p, ws, q, kk, lse, lse_out, c1, st);
   }
   if (p.dtype == ASL_BF16)
     return launch_score_generic<__bf16>(p, ws, static_cast<const __bf16*>(q_obs),
-                                        static_cast<const __bf16*>(k), lse, c1, st);
+                                        static_cast<const __bf16*>(k), lse, lse_out, c1, st);
   return launch_score_generic<float>(p, ws, static_cast<const float*>(q_obs),
-                                     static_cast<const float*>(k), lse, c1, st);
+                                     static_cast<const float*>(k), lse, lse_out, c1, st);
 }
 
 }  // namespace asl

@@ -184,19 +184,24 @@ def config_layer(config: int, strong_needles: bool = True) -> Layer:
 
 
 # --------------------------------------------------------------------------- config 4: layer sweep
-def sweep_rho(layer: int, n_layers: int = 32) -> float:
-    """Linear correlation schedule 0.2 -> 0.95 over the layers."""
-    return 0.2 + 0.75 * layer / (n_layers - 1)
+SWEEP_RHO_END = 0.95          # the stated schedule ends here
+SWEEP_RHO_END_CONVERGED = 0.985   # labelled variant: the last layers are almost identical
 
 
-def sweep_latents(T: int, n_layers: int = 32, seed: int = BASE_SEED + 4) -> np.ndarray:
+def sweep_rho(layer: int, n_layers: int = 32, rho_end: float = SWEEP_RHO_END) -> float:
+    """Linear correlation schedule 0.2 -> rho_end over the layers."""
+    return 0.2 + (rho_end - 0.2) * layer / (n_layers - 1)
+
+
+def sweep_latents(T: int, n_layers: int = 32, seed: int = BASE_SEED + 4,
+                  rho_end: float = SWEEP_RHO_END) -> np.ndarray:
     """AR(1) latent importance z_l in R^T per layer: z_l = rho_l z_{l-1} + sqrt(1-rho_l^2) eps_l,
     z_{-1} a shared seeded N(0,1) vector.  Returns [n_layers, T] float64."""
     rng = np.random.Generator(np.random.PCG64(seed))
     z = rng.standard_normal(T)
     out = np.empty((n_layers, T), dtype=np.float64)
     for l in range(n_layers):
-        rho = sweep_rho(l, n_layers)
+        rho = sweep_rho(l, n_layers, rho_end)
         z = rho * z + math.sqrt(1.0 - rho * rho) * rng.standard_normal(T)
         out[l] = z
     return out

@@ -13,7 +13,9 @@ pytestmark = pytest.mark.gpu
 
 
 def _rank_order_consistent(rank_gpu: np.ndarray, s_ref: np.ndarray, what: str):
-    """Tokens taken in GPU rank order must have non-increasing oracle scores up to the tolerance."""
+    """Tokens taken in GPU rank order must have non-increasing oracle scores up to the score tolerance:
+    a token may precede, in the GPU's order, only tokens whose oracle score exceeds its own by at most
+    1e-5 + 2e-3 |score|."""
     T = s_ref.shape[0]
     assert np.array_equal(np.sort(rank_gpu), np.arange(T)), f"{what}: ranks are not a permutation"
     if T < 2:
@@ -22,9 +24,10 @@ def _rank_order_consistent(rank_gpu: np.ndarray, s_ref: np.ndarray, what: str):
     order[rank_gpu] = np.arange(T)
     so = s_ref[order]
     prefmin = np.minimum.accumulate(so)
-    tol = 2 * (gu.ATOL + gu.RTOL * np.abs(so))
-    viol = so[1:] - prefmin[:-1] - tol[1:]
-    assert viol.max() <= 0, f"{what}: rank order contradicts oracle scores by {viol.max()}"
+    tol = gu.ATOL + gu.RTOL * np.abs(so)
+    excess = (so[1:] - prefmin[:-1]) / tol[1:]
+    gu.note_margin(f"{what} rank-order inversion", max(float(excess.max()), 0.0))
+    assert excess.max() <= 1.0, f"{what}: rank order contradicts oracle scores by {excess.max()} x tolerance"
 
 
 def _pipeline(dev, L, layer_idx=0, ctx=None, state=None, ring=None, l_min=None, l_obs=None, tau=None):
@@ -99,6 +102,7 @@ def test_config_chain(gpu_device, cfg):
     print(f"chain {L.name}", flush=True)
     out = _pipeline(gpu_device, L)
     _check_layer(L, out)
+    gu.report_margins(L.name)
 
 
 def test_one_million_tokens(gpu_device):
@@ -150,50 +154,76 @@ def test_config3_literal_needles_are_not_recoverable(gpu_device):
     ctx.close()
 
 
-def test_config4_sweep_selection_layer(gpu_device):
-    """32-layer sweep through the whole pipeline: the GPU must pick the same selection layer as the
-    oracle.  With this recipe the relative variance falls to about 0.34 at the last layer, so the
-    run uses tau = 0.5 from the paper's ablation grid (selection near layer 29); the first-crossing
-    layer is also compared for the other grid values whose oracle margin is large enough to make
-    the agreement meaningful."""
+def _sweep_through_pipeline(dev, tau, rho_end, what):
+    """The 32-layer sweep through the whole pipeline.  Returns the oracle's selection layer after
+    asserting that the GPU agrees with it at every layer.
+    The chained statistic is not a score: it depends on the ranks of tens of thousands of tokens
+    whose scores are closer together than the score tolerance, so GPU and oracle ranks (hence
+    var_top) legitimately differ a little.  The decision must be identical wherever the oracle's
+    relative variance is at least 1e-3 away from tau (asserted first); the statistic itself is
+    compared at 2 % relative as a sanity bound and the worst observed deviation is printed.  Its
+    exactness is established by the stage-isolated tests, which feed identical ranks to both sides."""
     import torch
     sh = synth.shape_of(4)
-    tau = 0.5
-    z = synth.sweep_latents(sh.T, sh.n_layers)
+    z = synth.sweep_latents(sh.T, sh.n_layers, rho_end=rho_end)
     ctx = gu.ctx_for(sh)
-    ring = torch.zeros((sh.L_obs, sh.T), dtype=torch.int32, device=gpu_device)
-    state = asl.new_state(gpu_device)
+    ring = torch.zeros((sh.L_obs, sh.T), dtype=torch.int32, device=dev)
+    state = asl.new_state(dev)
     ost = orc.SelectState.new(sh.L_obs)
     sel_gpu = sel_ref = None
     rel_ref, rel_gpu = {}, {}
+    worst_rel = 0.0
     for l in range(sh.n_layers):
         L = synth.sweep_layer(sh, z[l], l)
-        out = _pipeline(gpu_device, L, layer_idx=l, ctx=ctx, state=state, ring=ring, tau=tau)
+        out = _pipeline(dev, L, layer_idx=l, ctx=ctx, state=state, ring=ring, tau=tau)
         _, s_ref = orc.score_layer(L.q_obs, L.k, sh.W, sh.S)
-        gu.assert_scores_close(out["s"], s_ref, f"sweep layer {l} s")
+        gu.assert_scores_close(out["s"], s_ref, f"{what} s")
         ost.push(l, orc.rank_desc(s_ref))
         d = orc.select_tokens(ost, l, sh.budget, sh.W, sh.L_min, tau)
         st = out["stat"]
-        print(f"layer {l}: oracle rel={d.rel_var:.4f} gpu rel={st.rel_var:.4f} union {d.union_size}/{st.union_size}",
+        print(f"{what} layer {l}: oracle rel={d.rel_var:.4f} gpu rel={st.rel_var:.4f} union {d.union_size}/{st.union_size}",
               flush=True)
         assert bool(st.evaluated) == d.evaluated
         if d.evaluated:
             rel_ref[l], rel_gpu[l] = d.rel_var, st.rel_var
             assert abs(d.rel_var - tau) > 1e-3, "oracle decision too close to tau: reseed"
-            assert abs(st.rel_var - d.rel_var) < 2e-2 * max(d.rel_var, 1e-3)
+            dev_rel = abs(st.rel_var - d.rel_var) / max(d.rel_var, 1e-3)
+            worst_rel = max(worst_rel, dev_rel)
+            assert dev_rel < 2e-2
             assert bool(st.selected) == d.selected
         if d.selected:
             sel_ref, sel_gpu = l, (l if st.selected else None)
-            gu.check_topk_within_tolerance(out["I_all"], s_ref, sh.k, "sweep selection top-k")
+            gu.check_topk_within_tolerance(out["I_all"], s_ref, sh.k, f"{what} selection top-k")
             break
+    print(f"{what}: worst relative deviation of the chained relative variance {worst_rel:.3g}", flush=True)
+    gu.report_margins(what)
     assert sel_ref is not None and sh.L_min < sel_ref <= 31 and sel_gpu == sel_ref
     assert asl.read_struct(state, asl.AslState).n_valid_rows == 0      # rank cache released
     assert rel_ref[sh.L_min] == 1.0 and rel_gpu[sh.L_min] == 1.0       # relative variance is 1 at L_min
+    ctx.close()
+    return sel_ref, rel_ref, rel_gpu
+
+
+def test_config4_sweep_selection_layer(gpu_device):
+    """32-layer sweep through the whole pipeline with the stated correlation schedule (0.2 -> 0.95):
+    the GPU must pick the same selection layer as the oracle.  With this recipe the relative variance
+    falls to about 0.34 at the last layer, so the run uses tau = 0.5 from the paper's ablation grid
+    (selection near layer 29); the first-crossing layer is also compared for the other grid values
+    whose oracle margin is large enough to make the agreement meaningful."""
+    _, rel_ref, rel_gpu = _sweep_through_pipeline(gpu_device, 0.5, synth.SWEEP_RHO_END, "sweep tau=0.5")
     first = lambda rel, t: next((l for l in sorted(rel) if rel[l] < t), None)
     for t in (0.6, 0.7, 0.8, 0.9):
         if min(abs(r - t) for r in rel_ref.values()) > 1e-3:
             assert first(rel_ref, t) == first(rel_gpu, t)
-    ctx.close()
+
+
+def test_config4_variant_selects_at_default_tau(gpu_device):
+    """LABELLED VARIANT of the sweep: the correlation schedule ends at SWEEP_RHO_END_CONVERGED instead
+    of 0.95, everything else as stated, so that the relative variance of the full pipeline does fall
+    below the paper's default tau = 0.3 (Sec. 5.1) before the last layer is over, and the selection
+    happens after L_min and at or before layer 31."""
+    sel, _, _ = _sweep_through_pipeline(gpu_device, 0.3, synth.SWEEP_RHO_END_CONVERGED, "sweep-variant tau=0.3")
+    assert sel > synth.shape_of(4).L_min
 
 
 def test_sweep_score_level_bit_exact(gpu_device):
@@ -364,9 +394,107 @@ def test_hidden_state_propagation(gpu_device):
     ctx.close()
 
 
+def test_two_pass_handoff_from_a_selecting_step(gpu_device):
+    """Sec. 4.2, two-pass variant: the first pass runs layer steps until one selects; its select_idx
+    (row Hk of idx_out, valid because out->selected is set) then picks the rows of the embedding
+    matrix from which the second pass restarts at layer 0.  Score-correlated layers make the
+    statistic collapse, so the step at the last layer really selects."""
+    import torch
+    dev = gpu_device
+    sh = synth.Shape(Hq=8, Hk=2, d=128, N=6000, W=32, S=7, budget=512, L_obs=4, L_min=3, tau=0.3)
+    rng = np.random.default_rng(9)
+    base = synth.iid_layer(sh, 500, name="two-pass")
+    ctx = asl.Asl(sh.N, sh.Hk + 1, sh.Hq * sh.W)
+    p = gu.params_of(sh)
+    T, n_idx = sh.T, sh.k + sh.W
+    qd = gu.to_dev(base.q_obs, "bf16", dev)
+    scores = torch.empty((sh.Hk + 1, T), dtype=torch.float32, device=dev)
+    ring = torch.zeros((sh.L_obs, T), dtype=torch.int32, device=dev)
+    state, stat = asl.new_state(dev), asl.new_stat(dev)
+    I = torch.empty((sh.Hk + 1, n_idx), dtype=torch.int32, device=dev)
+    ost = orc.SelectState.new(sh.L_obs)
+    selected_at = None
+    for l in range(12):
+        # layers 0-3 have unrelated keys, from layer 4 on every layer sees the same keys: the ranks stop moving
+        kl = synth.iid_layer(sh, 600 + l).k if l < 4 else base.k
+        kd, vd = gu.to_dev(kl, "bf16", dev), gu.to_dev(base.v, "bf16", dev)
+        ctx.asl_layer_step(p, qd, kd, vd, l, sh.L_min, sh.L_obs, sh.tau, scores, ring, state, stat, I)
+        torch.cuda.synchronize()
+        sg = scores[sh.Hk].cpu().numpy().astype(np.float64)
+        ost.push(l, orc.rank_desc(sg))                     # the oracle's Alg. 2 on the GPU's own scores: exact
+        d = orc.select_tokens(ost, l, sh.budget, sh.W, sh.L_min, sh.tau)
+        st = asl.read_struct(stat, asl.AslStat)
+        assert bool(st.evaluated) == d.evaluated and bool(st.selected) == d.selected
+        if d.evaluated:
+            assert st.var_top == d.var_top and st.rel_var == d.rel_var and st.union_size == d.union_size
+        if d.selected:
+            selected_at = l
+            break
+    assert selected_at is not None and selected_at > sh.L_min
+    select_idx = I[sh.Hk]
+    np.testing.assert_array_equal(select_idx.cpu().numpy().astype(np.int64), d.select_idx)
+    # second pass input: the embeddings of the selected tokens only
+    D = 1024
+    emb = synth.round_bf16(rng.standard_normal((sh.N, D)).astype(np.float32))
+    embd = gu.to_dev(emb, "bf16", dev)
+    out = torch.zeros((n_idx, D), dtype=torch.bfloat16, device=dev)
+    ctx.asl_gather_rows(embd, D * 2, D * 2, select_idx, n_idx, out)
+    assert np.array_equal(out.float().cpu().numpy(), orc.propagate_tokens(emb, d.select_idx))
+    ctx.close()
+
+
+@pytest.mark.parametrize("shared_idx", [False, True])
+def test_gather_many_layers_from_separate_allocations(gpu_device, shared_idx):
+    """asl_gather_kv_layers: every layer's K/V cache is its own allocation, named by a device array of
+    pointers; the result must equal the per-layer oracle gather bit for bit, and the single-layer call."""
+    import torch
+    dev = gpu_device
+    n_layers, Hk, N, d, n_idx = 5, 3, 1777, 128, 301
+    rng = np.random.default_rng(17)
+    sh = synth.Shape(Hq=Hk, Hk=Hk, d=d, N=N, W=8, S=7, budget=n_idx)
+    ctx = gu.ctx_for(sh)
+    p = gu.params_of(sh)
+    ks, vs, kd, vd, ko, vo = [], [], [], [], [], []
+    pad = []                                                    # odd-sized allocations between the caches
+    for l in range(n_layers):
+        ks.append(synth.round_bf16(rng.standard_normal((Hk, N, d)).astype(np.float32)))
+        vs.append(synth.round_bf16(rng.standard_normal((Hk, N, d)).astype(np.float32)))
+        kd.append(gu.to_dev(ks[-1], "bf16", dev))
+        pad.append(torch.empty(4096 * (l + 1) + 48, dtype=torch.uint8, device=dev))
+        vd.append(gu.to_dev(vs[-1], "bf16", dev))
+        ko.append(torch.zeros((Hk, n_idx, d), dtype=torch.bfloat16, device=dev))
+        vo.append(torch.zeros((Hk, n_idx, d), dtype=torch.bfloat16, device=dev))
+    rows = 1 if shared_idx else Hk
+    idx = np.stack([np.stack([np.sort(rng.choice(N, n_idx, replace=False)) for _ in range(rows)])
+                    for _ in range(n_layers)]).astype(np.int32)
+    idxd = torch.from_numpy(idx).to(dev)
+    ptrs = lambda ts: torch.tensor([t.data_ptr() for t in ts], dtype=torch.int64, device=dev)
+    ctx.asl_gather_kv_layers(p, ptrs(kd), ptrs(vd), idxd, rows, n_idx, n_layers, ptrs(ko), ptrs(vo))
+    torch.cuda.synchronize()
+    k1 = torch.zeros_like(ko[0])
+    v1 = torch.zeros_like(vo[0])
+    for l in range(n_layers):
+        ref_k, ref_v = orc.gather_kv(ks[l], vs[l], idx[l, 0] if shared_idx else idx[l])
+        assert np.array_equal(ko[l].float().cpu().numpy(), ref_k), f"layer {l} K"
+        assert np.array_equal(vo[l].float().cpu().numpy(), ref_v), f"layer {l} V"
+        ctx.asl_gather_kv(p, kd[l], vd[l], idxd[l], rows, n_idx, k1, v1)
+        assert torch.equal(k1, ko[l]) and torch.equal(v1, vo[l])
+    # K only, and an empty call
+    ko2 = [torch.zeros_like(t) for t in ko]
+    ctx.asl_gather_kv_layers(p, ptrs(kd), None, idxd, rows, n_idx, n_layers, ptrs(ko2), None)
+    ctx.asl_gather_kv_layers(p, ptrs(kd), None, idxd, rows, n_idx, 0, ptrs(ko2), None)
+    torch.cuda.synchronize()
+    for l in range(n_layers):
+        assert torch.equal(ko2[l], ko[l])
+    with pytest.raises(asl.AslError):
+        ctx.asl_gather_kv_layers(p, ptrs(kd), ptrs(vd), idxd, rows, n_idx, n_layers, ptrs(ko), None)
+    ctx.close()
+
+
 def test_ring_restart_and_cyclic_continuity(gpu_device):
-    """A layer index whose ring row does not follow the previous one restarts the rank cache; indices
-    that wrap round the ring (as in a replayed graph of L_obs layers) keep it."""
+    """Only the next layer index, or the same index one trip round the ring earlier (a replayed graph
+    of L_obs layers), continues the rank cache; any other index restarts it, also one whose ring row
+    happens to be the next one."""
     import torch
     sh = synth.shape_of(1)
     ctx = gu.ctx_for(sh)
@@ -375,19 +503,30 @@ def test_ring_restart_and_cyclic_continuity(gpu_device):
     rng = np.random.default_rng(0)
     ring = torch.zeros((L_obs, T), dtype=torch.int32, device=gpu_device)
     state, stat = asl.new_state(gpu_device), asl.new_stat(gpu_device)
+    rows = {}
     def push(layer):
-        s = torch.from_numpy(rng.random(T, dtype=np.float32)).to(gpu_device)
-        ctx.asl_rank_stat(p, s, layer, 0, L_obs, 0.0, ring, state, stat)
+        s = rng.random(T, dtype=np.float32)
+        rows[layer % L_obs] = orc.rank_desc(s.astype(np.float64))
+        ctx.asl_rank_stat(p, torch.from_numpy(s).to(gpu_device), layer, 0, L_obs, 0.0, ring, state, stat)
         return asl.read_struct(state, asl.AslState), asl.read_struct(stat, asl.AslStat)
     assert push(0)[0].n_valid_rows == 1
     assert push(1)[0].n_valid_rows == 2
     st, out = push(2)
     assert st.n_valid_rows == 3 and out.evaluated == 1 and out.n_rows == 3
     assert push(3)[0].n_valid_rows == 4
-    assert push(0)[0].n_valid_rows == 4            # wraps round the ring: still consecutive rows
-    assert push(5)[0].n_valid_rows == 4            # 5 % 4 == 1 follows 0
-    st, out = push(7)                              # 7 % 4 == 3 does not follow 1: restart
-    assert st.n_valid_rows == 1 and st.last_layer == 7 and out.evaluated == 0
+    st, out = push(0)                              # 0 == 3 + 1 - L_obs: a replayed trip, still consecutive rows
+    assert st.n_valid_rows == 4 and out.n_rows == 4
+    ref = orc.rank_variance(np.stack([rows[r] for r in (1, 2, 3, 0)]), sh.k)
+    assert out.numerator == ref.numerator and out.union_size == ref.union_size
+    assert push(1)[0].n_valid_rows == 4
+    st, out = push(6)                              # 6 % 4 == 2 is the next ring row, but 6 != 1 + 1: restart
+    assert st.n_valid_rows == 1 and st.last_layer == 6 and out.evaluated == 0
+    st, out = push(7)
+    assert st.n_valid_rows == 2 and out.evaluated == 1 and out.n_rows == 2
+    ref = orc.rank_variance(np.stack([rows[2], rows[3]]), sh.k)
+    assert out.numerator == ref.numerator and out.union_size == ref.union_size
+    st, out = push(16)                             # a jump by a multiple of L_obs plus one: restart as well
+    assert st.n_valid_rows == 1 and out.evaluated == 0
     ctx.close()
 
 

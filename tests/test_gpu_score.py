@@ -147,8 +147,83 @@ def test_config2_full(gpu_device):
 def test_config3_full_128k(gpu_device):
     L = synth.config_layer(3)
     _compare(gpu_device, L)
+    gu.report_margins(L.name)
+
+
+def test_config3_lse_supplied_128k(gpu_device):
+    """The one-pass mode at the size the benchmark times it: the rows' log-sum-exp comes from the
+    oracle (float64, rounded to fp32), K is streamed once."""
+    L = synth.config_layer(3)
+    L.name += "-lse"
+    _compare(gpu_device, L, use_lse=True)
+    gu.report_margins(L.name)
+
+
+def _window_lse(dev, L, flags=0):
+    import torch
+    sh = L.shape
+    ctx = gu.ctx_for(sh)
+    p = gu.params_of(sh, flags=flags)
+    qd, kd = gu.to_dev(L.q_obs, sh.dtype, dev), gu.to_dev(L.k, sh.dtype, dev)
+    lse = torch.full((sh.Hq, sh.W), float("nan"), dtype=torch.float32, device=dev)
+    ctx.asl_window_lse(p, qd, kd, lse)
+    P0 = torch.empty((sh.Hk, sh.T), dtype=torch.float32, device=dev)
+    s0 = torch.empty((sh.T,), dtype=torch.float32, device=dev)
+    P1, s1 = torch.empty_like(P0), torch.empty_like(s0)
+    ctx.asl_score_layer(p, qd, kd, P0, s0)                       # self-contained: two passes over K
+    ctx.asl_score_layer(p, qd, kd, P1, s1, lse=lse)              # with the library's own log-sum-exp
+    torch.cuda.synchronize()
+    ctx.close()
+    return lse.cpu().numpy().astype(np.float64), (P0, s0), (P1, s1)
+
+
+@pytest.mark.parametrize("case", ["small-d64", "ragged-rows", "w64", "f32-plain", "heavy-tail", "c2"])
+def test_window_lse_matches_oracle_and_hands_back_exactly(gpu_device, case):
+    """asl_window_lse against the oracle's log-sum-exp of the masked, scaled logits (fp32 accumulation
+    of a sum of N positive terms: 1e-5 absolute + 2e-6 relative on a logarithm), and the hand-off:
+    scoring with these values supplied is bit-identical to the self-contained call."""
+    import torch
+    if case == "small-d64":
+        L = _small(4, 2, 64, 700, 16, seed=21)
+    elif case == "ragged-rows":
+        L = _small(7, 1, 128, 2500, 32, seed=22)                 # 224 query rows per KV head
+    elif case == "w64":
+        L = _small(8, 2, 128, 4096 + 77, 64, seed=23)
+    elif case == "f32-plain":
+        L = _small(4, 2, 64, 700, 16, dtype="f32", seed=24)
+    elif case == "heavy-tail":
+        sh = synth.Shape(Hq=8, Hk=2, d=128, N=6000, W=64, S=7, budget=512)
+        L = synth.needle_layer(sh, 11, 16, synth.needle_gain_strong(sh), heavy_tail=True, name="heavy")
+    else:
+        L = synth.config_layer(2)
+    sh = L.shape
+    lse, (P0, s0), (P1, s1) = _window_lse(gpu_device, L)
+    ref = orc.row_lse(L.q_obs, L.k, sh.W)
+    err = np.abs(lse - ref)
+    assert np.all(err <= 1e-5 + 2e-6 * np.abs(ref)), f"{case}: worst lse error {err.max()}"
+    assert torch.equal(P0, P1) and torch.equal(s0, s1), f"{case}: hand-back is not bit-identical"
 
 
 def test_config5_full_256k(gpu_device):
     L = synth.config_layer(5)
     _compare(gpu_device, L)
+    gu.report_margins(L.name)
+
+
+# The 28-layer model's head geometry (App. B.3: 4 KV heads, 7 query heads per group) at the paper's
+# long contexts: 224 query rows per KV head at window 32, 448 at window 64.
+@pytest.mark.parametrize("N,W,budget", [(131072, 32, 8192), (262144, 64, 8192)])
+def test_second_model_geometry_full_size(gpu_device, N, W, budget):
+    sh = synth.Shape(Hq=28, Hk=4, d=128, N=N, W=W, S=7, budget=budget, L_min=9)
+    L = synth.needle_layer(sh, 91 + W, 64, synth.needle_gain_strong(sh), name=f"qwen-like-N{N}-W{W}")
+    print(f"score {L.name}", flush=True)
+    _compare(gpu_device, L)
+    gu.report_margins(L.name)
+
+
+@pytest.mark.parametrize("Hq,Hk,W", [(5, 1, 64), (6, 1, 64), (16, 2, 64), (12, 1, 32), (7, 1, 48)])
+def test_row_counts_up_to_512(gpu_device, Hq, Hk, W):
+    """G*W = 320, 384, 512, 384, 336 query rows per KV head: five to eight wavefronts of two 32-row
+    blocks, with and without padded rows."""
+    _compare(gpu_device, _small(Hq, Hk, 128, 3000 + 13 * Hq, W, seed=30 + Hq))
+    _compare(gpu_device, _small(Hq, Hk, 64, 1500 + 7 * Hq, W, seed=40 + Hq))

@@ -194,6 +194,56 @@ def test_fewer_than_two_rows_not_evaluated():
     assert not d.evaluated and st.init_var is None
 
 
+def test_cache_released_after_selection():
+    """Alg. 2 step 13: the selection empties the rank cache; the next layer's push starts from a
+    single row, which is not evaluated (fewer than two rows) and leaves init_var untouched."""
+    T, W, budget = 120, 4, 24
+    rng = np.random.default_rng(11)
+    st = orc.SelectState.new(4)
+    base = rng.permutation(T)
+    st.push(0, rng.permutation(T))
+    st.push(1, rng.permutation(T))
+    d = orc.select_tokens(st, 1, budget, W, L_min=1, tau=0.3)     # first evaluation: rel = 1, no selection
+    assert d.evaluated and not d.selected and d.rel_var == 1.0 and len(st.rows) == 2
+    init = st.init_var
+    for l in (2, 3, 4, 5):                                         # identical rows: variance collapses to 0
+        st.push(l, base)
+        d = orc.select_tokens(st, l, budget, W, L_min=1, tau=0.3)
+        if d.selected:
+            break
+    assert d.selected and l == 5 and d.var_top == 0.0              # the 4-row window holds 4 equal rows
+    assert st.rows == [] and st.init_var == init                   # step 13: cache cleared, init_var kept
+    k = budget - W
+    np.testing.assert_array_equal(d.select_idx[:k], np.sort(np.argsort(base, kind="stable")[:k]))
+    st.push(6, rng.permutation(T))
+    d = orc.select_tokens(st, 6, budget, W, L_min=1, tau=0.3)
+    assert len(st.rows) == 1 and not d.evaluated and d.n_rows == 1 and d.select_idx is None
+    assert st.init_var == init
+
+
+@pytest.mark.parametrize("rows_available", [2, 3, 5])
+def test_partial_window_uses_the_rows_available(rows_available):
+    """Evaluation at L_min with 2 <= rows < L_obs rows in the cache: n is the number of rows
+    held, and var_top is the brute-force mean variance over those rows only."""
+    T, W, budget, L_obs = 90, 6, 20, 8
+    rng = np.random.default_rng(20 + rows_available)
+    st = orc.SelectState.new(L_obs)
+    R = [rng.permutation(T) for _ in range(rows_available)]
+    for l, r in enumerate(R):
+        st.push(l, r)
+    d = orc.select_tokens(st, rows_available - 1, budget, W, L_min=rows_available - 1, tau=0.3)
+    assert d.evaluated and d.n_rows == rows_available and d.rel_var == 1.0
+    want, m = _brute_rank_variance(np.stack(R), budget - W)
+    assert d.union_size == m
+    assert abs(d.var_top - float(want)) <= 1e-12 * float(want)
+    # one more row: the window grows by one (still below L_obs) and the divisor stays init_var
+    st.push(rows_available, rng.permutation(T))
+    d2 = orc.select_tokens(st, rows_available, budget, W, L_min=rows_available - 1, tau=0.0)
+    assert d2.n_rows == rows_available + 1
+    want2, _ = _brute_rank_variance(np.stack([r for _, r in st.rows]), budget - W)
+    assert abs(d2.rel_var - float(want2 / want)) <= 1e-12 * float(want2 / want)
+
+
 # ----------------------------------------------------------------------------- top-k, gather
 def test_topk_exhaustive_small():
     """All score vectors over a 3-letter alphabet of length 6, every k: compare with the
@@ -221,20 +271,33 @@ def test_select_indices_rows_and_window():
         np.testing.assert_array_equal(I[g, :5], orc.topk_indices(P[g], 5))
 
 
-def test_gather_is_fancy_indexing():
+def test_gather_matches_element_loop():
+    """Alg. 1 step 12 element by element: out[g, i, c] = k[g, idx[g or shared, i], c], with
+    repeated and unsorted indices and per-head rows that differ from each other."""
     rng = np.random.default_rng(6)
     k = rng.standard_normal((3, 20, 4))
     v = rng.standard_normal((3, 20, 4))
-    idx = np.array([[1, 5, 19], [0, 2, 3], [7, 8, 9]])
+    idx = np.array([[1, 5, 19, 5], [0, 2, 3, 0], [9, 8, 7, 19]])
     ko, vo = orc.gather_kv(k, v, idx)
+    assert ko.shape == vo.shape == (3, 4, 4)
     for g in range(3):
-        np.testing.assert_array_equal(ko[g], k[g][idx[g]])
-        np.testing.assert_array_equal(vo[g], v[g][idx[g]])
-    ko, vo = orc.gather_kv(k, v, np.arange(20))
+        for i in range(4):
+            for c in range(4):
+                assert ko[g, i, c] == k[g, idx[g, i], c]
+                assert vo[g, i, c] == v[g, idx[g, i], c]
+    shared = np.array([4, 2, 4])                                   # one index row for every head
+    ko, vo = orc.gather_kv(k, v, shared)
+    assert ko.shape == (3, 3, 4)
+    for g in range(3):
+        for i in range(3):
+            for c in range(4):
+                assert ko[g, i, c] == k[g, shared[i], c]
+                assert vo[g, i, c] == v[g, shared[i], c]
+    ko, vo = orc.gather_kv(k, v, np.arange(20))                    # identity selection
     np.testing.assert_array_equal(ko, k)
     np.testing.assert_array_equal(vo, v)
-    ko, _ = orc.gather_kv(k, v, np.array([4, 2]))                 # shared index row
-    np.testing.assert_array_equal(ko, k[:, [4, 2], :])
+    ko[0, 0, 0] = 99.0                                             # a copy, not a view
+    assert k[0, 0, 0] != 99.0
 
 
 def test_propagate_tokens_is_row_selection():
