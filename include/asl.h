@@ -123,9 +123,10 @@ asl_status asl_score_layer(asl_ctx* ctx, const asl_params* params, const void* q
  * all N keys of window row i of query head h's scaled, causally masked logits (the first of
  * asl_score_layer's two passes over K; fp32, deterministic).
  *   q_obs, k as in asl_score_layer;  lse_out [Hq, W] f32 out.
- * Handing lse_out back to asl_score_layer as `lse` gives bit-identical scores to the self-contained
- * call.  For callers that score one K against the same window more than once, and as the reference
- * for an attention kernel that produces these values itself. */
+ * Handing lse_out back to asl_score_layer as `lse` gives the scores of the self-contained call up
+ * to the fp32 rounding of the logarithm's change of base (relative differences of a few 1e-6).
+ * For callers that score one K against the same window more than once, and as the reference for
+ * an attention kernel that produces these values itself. */
 asl_status asl_window_lse(asl_ctx* ctx, const asl_params* params, const void* q_obs, const void* k,
                           float* lse_out, void* stream);
 
