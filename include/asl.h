@@ -139,6 +139,21 @@ asl_status asl_pool(asl_ctx* ctx, const float* u, int32_t rows, int32_t T, int32
  *   s [T] f32 in; rank_out [T] int32 out (a permutation of 0..T-1). */
 asl_status asl_rank(asl_ctx* ctx, const float* s, int32_t T, int32_t* rank_out, void* stream);
 
+/* asl_rank for callers that cannot allocate device memory: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  It needs no context: the sort's scratch buffers
+ * live in a static device array inside the library (about 4.1 MiB on every GPU the library runs
+ * on, held until the process ends), so the call allocates nothing, on the device or through any
+ * library.  Same result as asl_rank, bit for bit.
+ *   s [T] f32 in, rank_out [T] int32 out: device pointers on the CURRENT device; T <=
+ *   ASL_RANK_STATIC_MAX_T, larger T returns ASL_ENOMEM (message from asl_static_last_error, a
+ *   thread-local string).  The work is enqueued on `stream`.
+ * All calls on one GPU share that GPU's scratch array: calls that overlap on one GPU (different
+ * streams or threads) race; serialise them.  The array's device address is looked up on the first
+ * call per device (or by asl_create on that device); make that first call outside stream capture. */
+#define ASL_RANK_STATIC_MAX_T 262144
+asl_status asl_rank_static(const float* s, int32_t T, int32_t* rank_out, void* stream);
+const char* asl_static_last_error(void);
+
 /* Alg. 2 steps 4-10 on a rank ring that already holds this layer's row.
  *   rank_ring [l_obs, T] int32; the rows in use are those of layers
  *   layer_idx - state->n_valid_rows + 1 .. layer_idx, layer l living in row l % l_obs.

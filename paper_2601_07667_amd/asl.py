@@ -20,7 +20,7 @@ ASL_FLAG_DEFER_JOIN = 2
 _STATUS = {0: "ASL_OK", -1: "ASL_EINVAL", -2: "ASL_ENOMEM", -3: "ASL_EHIP", -4: "ASL_EUNSUPPORTED"}
 
 EXPORTS = ["asl_create", "asl_destroy", "asl_last_error", "asl_workspace_bytes", "asl_score_layer",
-           "asl_window_lse", "asl_gather_kv_layers", "asl_pool", "asl_rank", "asl_rankvar", "asl_rank_stat", "asl_select_topk", "asl_gather_kv",
+           "asl_window_lse", "asl_gather_kv_layers", "asl_rank_static", "asl_static_last_error", "asl_pool", "asl_rank", "asl_rankvar", "asl_rank_stat", "asl_select_topk", "asl_gather_kv",
            "asl_gather_rows", "asl_layer_step", "asl_join", "asl_profile_enable", "asl_profile_collect"]
 
 
@@ -80,6 +80,10 @@ def load() -> C.CDLL:
     lib.asl_pool.restype = C.c_int
     lib.asl_rank.argtypes = [vp, vp, i32, vp, vp]
     lib.asl_rank.restype = C.c_int
+    lib.asl_rank_static.argtypes = [vp, i32, vp, vp]
+    lib.asl_rank_static.restype = C.c_int
+    lib.asl_static_last_error.argtypes = []
+    lib.asl_static_last_error.restype = C.c_char_p
     lib.asl_rankvar.argtypes = [vp, vp, i32, i32, i32, i32, i32, C.c_double, vp, vp, vp]
     lib.asl_rankvar.restype = C.c_int
     lib.asl_rank_stat.argtypes = [vp, C.POINTER(AslParams), vp, i32, i32, i32, C.c_double, vp, vp, vp, vp]
@@ -208,6 +212,17 @@ class Asl:
     def asl_gather_kv(self, params: AslParams, k, v, idx, idx_rows: int, n_idx: int, k_out, v_out) -> None:
         self._check(self.lib.asl_gather_kv(self.h, C.byref(params), _ptr(k), _ptr(v), _ptr(idx), idx_rows,
                                            n_idx, _ptr(k_out), _ptr(v_out), _stream()))
+
+
+ASL_RANK_STATIC_MAX_T = 262144
+
+
+def asl_rank_static(s, T: int, rank_out) -> None:
+    """The context-free, allocation-free variant of asl_rank (scratch in a static device array)."""
+    lib = load()
+    st = lib.asl_rank_static(_ptr(s), T, _ptr(rank_out), _stream())
+    if st != ASL_OK:
+        raise AslError(st, lib.asl_static_last_error().decode())
 
 
 KERNEL_NAMES = ["score_rowstats", "score_combine", "score_colsum", "pool", "sort_hist", "sort_scatter",

@@ -169,6 +169,8 @@ asl_status asl_create(asl_ctx** out, int device, int32_t max_seq_len, int32_t ma
     delete ctx;
     return ASL_EHIP;
   }
+  (void)asl::rank_static_prepare(device);   // best effort: asl_rank_static looks it up itself otherwise
+  (void)hipGetLastError();
   ctx->side = nullptr;
   ctx->side_pending = false;
   ctx->ev_fork = ctx->ev_join = nullptr;

@@ -135,5 +135,7 @@ struct GatherArgs {
 hipError_t launch_gather(Prof* prof, const GatherArgs& args, int Hk, int n_layers, hipStream_t st);
 
 bool score_mfma_supported(const asl_params& p);
+// Looks up the device address of asl_rank_static's scratch array on `device` (which must be current).
+hipError_t rank_static_prepare(int device);
 
 }  // namespace asl

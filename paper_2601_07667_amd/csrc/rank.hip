@@ -6,6 +6,9 @@
 // rank[index] instead of writing the sorted pairs.  Per pass: a per-tile histogram kernel, then a
 // scatter kernel that derives its offsets from those histograms and ranks equal digits inside a
 // tile with wavefront ballots (stable by construction).
+#include <cstdio>
+#include <mutex>
+
 #include "asl_internal.h"
 
 namespace asl {
@@ -183,3 +186,85 @@ hipError_t launch_rank(const Workspace& ws, const float* s, int T, int32_t* rank
 }
 
 }  // namespace asl
+
+// ---------------------------------------------------------------------------------------------
+// asl_rank_static: asl_rank for callers that cannot allocate.  The sort's scratch (ping-pong
+// key/index buffers and the per-tile histograms) lives in a file-scope device array instead of a
+// context's workspace.  In host code the array's name is only a handle: its device address is
+// looked up once per device and that pointer is what the kernels get.
+namespace {
+
+constexpr int kStaticMaxT = ASL_RANK_STATIC_MAX_T;
+constexpr size_t kStaticTiles = (kStaticMaxT + asl::kSortTile - 1) / asl::kSortTile;
+constexpr size_t kStaticWords = 4 * (size_t)kStaticMaxT + 256 * kStaticTiles;
+static_assert(kStaticMaxT % 64 == 0, "keeps the four buffers 256-byte aligned");
+
+static __device__ __align__(256) uint32_t scratch[kStaticWords];
+
+constexpr int kMaxDevices = 64;
+uint32_t* g_scratch_ptr[kMaxDevices];            // device address of `scratch` on each device
+std::mutex g_scratch_mutex;
+thread_local char g_static_err[192] = "";
+
+// Device address of this device's copy of `scratch` (the current device must be `device`).
+hipError_t static_scratch(int device, uint32_t** out) {
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (g_scratch_ptr[device] == nullptr) {
+    void* ptr = nullptr;
+    const hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    g_scratch_ptr[device] = static_cast<uint32_t*>(ptr);
+  }
+  *out = g_scratch_ptr[device];
+  return hipSuccess;
+}
+
+asl_status static_fail(asl_status st, const char* msg, const char* detail = "") {
+  snprintf(g_static_err, sizeof(g_static_err), "%s%s", msg, detail);
+  return st;
+}
+
+}  // namespace
+
+namespace asl {
+hipError_t rank_static_prepare(int device) {
+  if (device < 0 || device >= kMaxDevices) return hipErrorInvalidDevice;
+  uint32_t* p = nullptr;
+  return static_scratch(device, &p);
+}
+}  // namespace asl
+
+extern "C" {
+#pragma GCC visibility push(default)
+
+asl_status asl_rank_static(const float* s, int32_t T, int32_t* rank_out, void* stream) {
+  if (!s || !rank_out) return static_fail(ASL_EINVAL, "asl_rank_static: null tensor pointer");
+  if (T < 1) return static_fail(ASL_EINVAL, "asl_rank_static: need T >= 1");
+  if (T > kStaticMaxT) {
+    char detail[64];
+    snprintf(detail, sizeof(detail), " (T=%d, limit %d)", T, kStaticMaxT);
+    return static_fail(ASL_ENOMEM, "asl_rank_static: T exceeds ASL_RANK_STATIC_MAX_T", detail);
+  }
+  int device = -1;
+  hipError_t e = hipGetDevice(&device);
+  if (e != hipSuccess) return static_fail(ASL_EHIP, "hipGetDevice: ", hipGetErrorString(e));
+  if (device < 0 || device >= kMaxDevices) return static_fail(ASL_EUNSUPPORTED, "asl_rank_static: device index too large");
+  uint32_t* base = nullptr;
+  e = static_scratch(device, &base);
+  if (e != hipSuccess) return static_fail(ASL_EHIP, "hipGetSymbolAddress(scratch): ", hipGetErrorString(e));
+  asl::Workspace ws = {};
+  ws.sort_key[0] = base;
+  ws.sort_idx[0] = base + (size_t)kStaticMaxT;
+  ws.sort_key[1] = base + 2 * (size_t)kStaticMaxT;
+  ws.sort_idx[1] = base + 3 * (size_t)kStaticMaxT;
+  ws.tile_hist = base + 4 * (size_t)kStaticMaxT;
+  ws.prof = nullptr;
+  e = asl::launch_rank(ws, s, T, rank_out, static_cast<hipStream_t>(stream));
+  if (e != hipSuccess) return static_fail(ASL_EHIP, "rank launch: ", hipGetErrorString(e));
+  return ASL_OK;
+}
+
+const char* asl_static_last_error(void) { return g_static_err; }
+
+#pragma GCC visibility pop
+}  // extern "C"
