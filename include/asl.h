@@ -241,11 +241,21 @@ asl_status asl_layer_step(asl_ctx* ctx, const asl_params* params, const void* q_
  * before the next layer starts; the compacted KV of a layer is needed at decoding time. */
 asl_status asl_join(asl_ctx* ctx, void* stream);
 
+/* Health check (not a step of the paper's method).  The workgroups of a ranking or statistic
+ * launch hand counts to each other inside the launch and wait for them with a bounded number
+ * of polls; a workgroup whose wait runs out raises a fault word in the workspace and writes no
+ * results (every wave still exits).  This call waits for the device to go idle, returns the word
+ * in *fault_out (0 = no wait ever ran out) and clears it.  Results of calls issued since the last
+ * check are valid iff it reads 0.  Synchronises: not for the hot loop. */
+asl_status asl_device_fault(asl_ctx* ctx, int32_t* fault_out);
+
 /* Measurement aid (not a step of the paper's method; for callers that time the kernels of the
  * calls above).  Kernel ids: 0 score row statistics (pass 1), 1 its combine, 2 score column sums
  * (pass 2), 3 pool, 4 sort histogram, 5 sort scatter, 6 rank-variance finalisation (or the
  * below-L_min skip), 7 rank-variance partial sums, 8 select histogram, 9 select write, 10 gather,
- * 11 plain-FMA score kernels.
+ * 11 plain-FMA score kernels.  (Each sort pass is one kernel, recorded under 5, id 4 is unused;
+ * 8 covers the top-k's bound and filter kernels, 9 its finishing kernel; the statistic is one
+ * kernel, 7; 6 is the below-L_min skip.)
  * asl_profile_enable: launches whose id bit is set in kernel_mask are bracketed by HIP events on
  *   the call's stream, up to max_records launches (further ones run unrecorded); mask 0 turns
  *   it off and frees the events.  Allocates host memory and events: not for the hot loop.

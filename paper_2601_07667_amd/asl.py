@@ -21,7 +21,7 @@ _STATUS = {0: "ASL_OK", -1: "ASL_EINVAL", -2: "ASL_ENOMEM", -3: "ASL_EHIP", -4: 
 
 EXPORTS = ["asl_create", "asl_destroy", "asl_last_error", "asl_workspace_bytes", "asl_score_layer",
            "asl_window_lse", "asl_gather_kv_layers", "asl_rank_static", "asl_static_last_error", "asl_pool", "asl_rank", "asl_rankvar", "asl_rank_stat", "asl_select_topk", "asl_gather_kv",
-           "asl_gather_rows", "asl_layer_step", "asl_join", "asl_profile_enable", "asl_profile_collect"]
+           "asl_gather_rows", "asl_layer_step", "asl_join", "asl_device_fault", "asl_profile_enable", "asl_profile_collect"]
 
 
 class AslParams(C.Structure):
@@ -97,6 +97,8 @@ def load() -> C.CDLL:
     lib.asl_layer_step.argtypes = [vp, C.POINTER(AslParams), vp, vp, vp, vp, i32, i32, i32, C.c_double,
                                    vp, vp, vp, vp, vp, vp, vp, vp]
     lib.asl_layer_step.restype = C.c_int
+    lib.asl_device_fault.argtypes = [vp, C.POINTER(i32)]
+    lib.asl_device_fault.restype = C.c_int
     lib.asl_join.argtypes = [vp, vp]
     lib.asl_join.restype = C.c_int
     lib.asl_profile_enable.argtypes = [vp, C.c_uint32, i32]
@@ -196,6 +198,12 @@ class Asl:
                                             layer_idx, l_min, l_obs, tau, _ptr(scores), _ptr(rank_ring),
                                             _ptr(state), _ptr(out), _ptr(idx_out), _ptr(k_out), _ptr(v_out),
                                             _stream()))
+
+    def asl_device_fault(self) -> int:
+        """Waits for the device, returns and clears the fault word (0 = every in-launch wait was met)."""
+        v = C.c_int32()
+        self._check(self.lib.asl_device_fault(self.h, C.byref(v)))
+        return v.value
 
     def asl_join(self) -> None:
         self._check(self.lib.asl_join(self.h, _stream()))

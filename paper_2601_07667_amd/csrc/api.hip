@@ -40,7 +40,6 @@ size_t carve(char* base, int32_t max_seq_len, int32_t max_kv_heads, int32_t max_
   const size_t N = (size_t)max_seq_len;
   const size_t rows = (size_t)(max_kv_heads > 1 ? max_kv_heads : 1);
   const size_t sort_tiles = (N + asl::kSortTile - 1) / asl::kSortTile;
-  const size_t sel_tiles = (N + asl::kSelTile - 1) / asl::kSelTile;
   asl::Workspace w;
   w.row_part = (float*)take((size_t)asl::kMaxChunks * max_q_rows * 2 * sizeof(float));
   w.row_const = (float*)take((size_t)max_q_rows * sizeof(float));
@@ -49,12 +48,17 @@ size_t carve(char* base, int32_t max_seq_len, int32_t max_kv_heads, int32_t max_
     w.sort_key[i] = (uint32_t*)take(N * sizeof(uint32_t));
     w.sort_idx[i] = (uint32_t*)take(N * sizeof(uint32_t));
   }
-  w.tile_hist = (uint32_t*)take(256 * sort_tiles * sizeof(uint32_t));   // [tile][256]
-  w.sel_hist = (uint32_t*)take(4 * rows * sel_tiles * 256 * sizeof(uint32_t));
-  w.sel_state = (uint32_t*)take(4 * rows * 2 * sizeof(uint32_t));
-  w.sel_tile_cnt = (uint32_t*)take(rows * sel_tiles * sizeof(uint32_t));
-  w.var_part_num = (unsigned long long*)take(asl::kVarMaxBlocks * sizeof(unsigned long long));
-  w.var_part_cnt = (uint32_t*)take(asl::kVarMaxBlocks * sizeof(uint32_t));
+  w.sort_table = (unsigned long long*)take(128 * sort_tiles * sizeof(unsigned long long));
+  w.sort_epoch = (unsigned long long*)take(sizeof(unsigned long long));
+  const size_t sel_tiles = (N + asl::kSelTile - 1) / asl::kSelTile;
+  w.sel_rows = (int)(rows < (size_t)asl::kSelMaxRowsAtOnce ? rows : (size_t)asl::kSelMaxRowsAtOnce);
+  w.sel_bound = (uint32_t*)take((size_t)w.sel_rows * sizeof(uint32_t));
+  w.sel_cand_key = (uint32_t*)take((size_t)w.sel_rows * sel_tiles * asl::kSelSegment * sizeof(uint32_t));
+  w.sel_cand_idx = (uint32_t*)take((size_t)w.sel_rows * sel_tiles * asl::kSelSegment * sizeof(uint32_t));
+  w.sel_seg_count = (uint32_t*)take((size_t)w.sel_rows * sel_tiles * sizeof(uint32_t));
+  w.var_table = (unsigned long long*)take((size_t)asl::kVarMaxBlocks * 4 * sizeof(unsigned long long));
+  w.var_epoch = (unsigned long long*)take(sizeof(unsigned long long));
+  w.fault = (uint32_t*)take(sizeof(uint32_t));
   if (ws) *ws = w;
   return off;
 }
@@ -161,8 +165,7 @@ asl_status asl_create(asl_ctx** out, int device, int32_t max_seq_len, int32_t ma
   }
   carve(static_cast<char*>(ctx->base), max_seq_len, max_kv_heads, max_q_rows, &ctx->ws);
   ctx->ws.prof = nullptr;
-  // nothing in the workspace needs an initial value; zero it once so that no run ever reads
-  // uninitialised memory
+  // the launch counters and the fault word start at zero; the rest needs no initial value
   e = hipMemset(ctx->base, 0, ctx->bytes);
   if (e != hipSuccess) {
     (void)hipFree(ctx->base);
@@ -349,6 +352,15 @@ asl_status asl_pool(asl_ctx* ctx, const float* u, int32_t rows, int32_t T, int32
   return ASL_OK;
 }
 
+// The workgroups of a sort launch (one per kSortTile elements) wait for each other, so they must
+// fit on the device at once.
+static asl_status check_sort_size(asl_ctx* ctx, int32_t T) {
+  if (T > asl::rank_max_tokens())
+    return fail(ctx, ASL_EUNSUPPORTED, "T=%d is more than one ranking launch can hold on this device (%lld tokens)", T,
+                (long long)asl::rank_max_tokens());
+  return ASL_OK;
+}
+
 asl_status asl_rank(asl_ctx* ctx, const float* s, int32_t T, int32_t* rank_out, void* stream) {
   if (!ctx) return ASL_EINVAL;
   if (!s || !rank_out) return fail(ctx, ASL_EINVAL, "null tensor pointer");
@@ -356,6 +368,8 @@ asl_status asl_rank(asl_ctx* ctx, const float* s, int32_t T, int32_t* rank_out, 
   if (T > ctx->max_seq_len) return fail(ctx, ASL_ENOMEM, "T=%d exceeds the context limit %d", T, ctx->max_seq_len);
   DeviceGuard guard(ctx->device);
   if (guard.err != hipSuccess) return hip_fail(ctx, guard.err, "set device");
+  asl_status st = check_sort_size(ctx, T);
+  if (st != ASL_OK) return st;
   hipError_t e = asl::launch_rank(ctx->ws, s, T, rank_out, static_cast<hipStream_t>(stream));
   if (e != hipSuccess) return hip_fail(ctx, e, "rank launch");
   return ASL_OK;
@@ -401,6 +415,8 @@ asl_status asl_rank_stat(asl_ctx* ctx, const asl_params* p, const float* s_all, 
   DeviceGuard guard(ctx->device);
   if (guard.err != hipSuccess) return hip_fail(ctx, guard.err, "set device");
   hipStream_t hs = static_cast<hipStream_t>(stream);
+  st = check_sort_size(ctx, T);
+  if (st != ASL_OK) return st;
   int32_t* row = rank_ring + (int64_t)(layer_idx % l_obs) * T;
   hipError_t e = asl::launch_rank(ctx->ws, s_all, T, row, hs);
   if (e != hipSuccess) return hip_fail(ctx, e, "rank launch");
@@ -576,6 +592,24 @@ asl_status asl_layer_step(asl_ctx* ctx, const asl_params* p, const void* q_obs, 
   if (st_side != ASL_OK) return st_side;
   if (st_main != ASL_OK) return st_main;
   if (e != hipSuccess) return hip_fail(ctx, e, "join");
+  return ASL_OK;
+}
+
+asl_status asl_device_fault(asl_ctx* ctx, int32_t* fault_out) {
+  if (!ctx) return ASL_EINVAL;
+  if (!fault_out) return fail(ctx, ASL_EINVAL, "null output pointer");
+  DeviceGuard guard(ctx->device);
+  if (guard.err != hipSuccess) return hip_fail(ctx, guard.err, "set device");
+  uint32_t v = 0;
+  hipError_t e = hipDeviceSynchronize();
+  if (e == hipSuccess) e = hipMemcpy(&v, ctx->ws.fault, sizeof(v), hipMemcpyDeviceToHost);
+  if (e != hipSuccess) return hip_fail(ctx, e, "fault word read");
+  *fault_out = (int32_t)v;
+  if (v != 0) {
+    const uint32_t zero = 0;
+    e = hipMemcpy(ctx->ws.fault, &zero, sizeof(zero), hipMemcpyHostToDevice);
+    if (e != hipSuccess) return hip_fail(ctx, e, "fault word reset");
+  }
   return ASL_OK;
 }
 

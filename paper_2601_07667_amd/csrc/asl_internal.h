@@ -55,13 +55,18 @@ struct Workspace {
   // radix sort (rank)
   uint32_t* sort_key[2];   // [T] ping-pong
   uint32_t* sort_idx[2];   // [T]
-  uint32_t* tile_hist;     // [n_tiles][256] per-tile digit histogram of the current sort pass
+  unsigned long long* sort_table;   // [n_tiles][128] tagged per-tile digit counts of the current pass
+  unsigned long long* sort_epoch;   // [1] tag of the last sort launch
   // select
-  uint32_t* sel_hist;      // [4 passes][rows][n_tiles][256]
-  uint32_t* sel_state;     // [4 passes][rows][2]  {prefix, keys still to take}
-  uint32_t* sel_tile_cnt;  // [rows][n_tiles] keys already known to lie below the threshold
-  unsigned long long* var_part_num;   // [kVarMaxBlocks] per-workgroup partial numerators
-  uint32_t* var_part_cnt;             // [kVarMaxBlocks] per-workgroup partial union counts
+  uint32_t* sel_bound;     // [sel_rows] key bound guessed from the row's sample
+  uint32_t* sel_cand_key;  // [sel_rows][n_tiles][kSelSegment] keys that passed the bound, in token order
+  uint32_t* sel_cand_idx;  // same shape: their token indices
+  uint32_t* sel_seg_count; // [sel_rows][n_tiles] entries used in each segment
+  int sel_rows;            // rows the candidate buffers hold at once
+  // rank variance
+  unsigned long long* var_table;    // [kVarMaxBlocks][2] tagged per-workgroup partial sums
+  unsigned long long* var_epoch;    // [1]
+  uint32_t* fault;         // [1] raised by a workgroup whose bounded wait for its peers ran out
   Prof* prof;              // null unless profiling is enabled
 };
 
@@ -71,10 +76,29 @@ struct Workspace {
 #ifndef ASL_SEL_TILE
 #define ASL_SEL_TILE 4096
 #endif
+#ifndef ASL_SORT_THREADS
+#define ASL_SORT_THREADS 1024
+#endif
 constexpr int kSortTile = ASL_SORT_TILE;   // elements per radix-sort workgroup tile (a multiple of 256)
 constexpr int kSelTile = ASL_SEL_TILE;     // elements per select workgroup tile (a multiple of 256)
 constexpr int kMaxChunks = 256;        // key chunks per KV head in scoring pass 1
-constexpr int kVarMaxBlocks = 512;     // workgroups of the rank-variance kernel
+constexpr int kVarMaxBlocks = 256;     // workgroups of the rank-variance kernel
+constexpr int kSortMaxTiles = 512;     // workgroups of one sort launch (they wait for each other)
+constexpr int kSelSegment = kSelTile / 2;   // candidate slots per select tile
+constexpr int kSelCandCap = 16384;     // candidates of one row the finishing workgroup holds in LDS
+constexpr int kSelMaxSample = 8192;    // sampled keys per row for the bound
+constexpr int kSelMaxRowTiles = 1024;  // tiles per row the candidate path handles
+constexpr int kSelMaxRowsAtOnce = 64;  // rows per round of select launches (bounds the candidate buffers)
+
+// ---- counts handed between workgroups of one launch -------------------------------------------
+// A 64-bit word = (tag << 28) | (count1 << 14) | count0, written and read whole with relaxed
+// device-scope atomic accesses.  The tag names the launch, so a reader can tell a fresh word from
+// whatever the table held before; nothing else has to be ordered or cleared.
+constexpr int kFlagCountBits = 14;
+constexpr int kFlagTagShift = 2 * kFlagCountBits;
+constexpr unsigned long long kFlagTagMask = (1ull << (64 - kFlagTagShift)) - 1ull;
+constexpr int kFlagBatch = 16;             // words a thread polls at once
+constexpr int kFlagSpinLimit = 1 << 17;    // polls before a waiter gives up (each takes ~1 us or more)
 
 
 // 256-bin digit histogram of a workgroup in LDS, kept in 8 copies (lane % 8 picks the copy, rows
@@ -98,13 +122,64 @@ __device__ __forceinline__ uint32_t hist_total(const uint32_t* h, int digit) {
   for (int c = 0; c < kHistCopies; ++c) t += h[c * kHistStride + digit];
   return t;
 }
+
+__device__ __forceinline__ void flag_publish(unsigned long long* p, unsigned long long tag, uint32_t c0,
+                                             uint32_t c1) {
+  const unsigned long long v = ((tag & kFlagTagMask) << kFlagTagShift) |
+                               ((unsigned long long)c1 << kFlagCountBits) | (unsigned long long)c0;
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ uint32_t flag_count0(unsigned long long v) {
+  return (uint32_t)v & ((1u << kFlagCountBits) - 1u);
+}
+__device__ __forceinline__ uint32_t flag_count1(unsigned long long v) {
+  return (uint32_t)(v >> kFlagCountBits) & ((1u << kFlagCountBits) - 1u);
+}
+// Reads the words  col[(t0 + u * STEP) * stride]  for u < kFlagBatch (those with t < n) until every
+// one carries `tag`.  Returns false if that has not happened after kFlagSpinLimit polls.
+template <int STEP>
+__device__ __forceinline__ bool flag_poll_batch(const unsigned long long* col, int stride, int t0, int n,
+                                                unsigned long long tag, unsigned long long (&v)[kFlagBatch]) {
+  const unsigned long long want = tag & kFlagTagMask;
+  for (int spins = 0;; ++spins) {
+    bool ok = true;
+#pragma unroll
+    for (int u = 0; u < kFlagBatch; ++u) {
+      const int t = t0 + u * STEP;
+      v[u] = (t < n) ? __hip_atomic_load(col + (int64_t)t * stride, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
+                     : (want << kFlagTagShift);
+    }
+#pragma unroll
+    for (int u = 0; u < kFlagBatch; ++u) ok = ok && ((v[u] >> kFlagTagShift) == want);
+    if (ok) return true;
+    if (spins >= kFlagSpinLimit) return false;
+    __builtin_amdgcn_s_sleep(1);
+  }
+}
 #endif
+
+// Workgroups of `kernel` that can wait for each other inside one launch: half of what the device
+// holds at once (other kernels may be running beside it), never more than `cap`.
+template <typename K>
+static inline int coresident_limit(K kernel, int threads, int cap = 1024) {
+  int dev = 0, cus = 0, per_cu = 0;
+  if (hipGetDevice(&dev) != hipSuccess ||
+      hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+      hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, threads, 0) != hipSuccess) {
+    (void)hipGetLastError();
+    return 1;
+  }
+  const long n = (long)cus * per_cu / 2;
+  return (int)(n < 1 ? 1 : (n > cap ? cap : n));
+}
 
 hipError_t launch_score(const asl_params& p, const Workspace& ws, const void* q_obs, const void* k,
                         const float* lse, float* lse_out, hipStream_t st);
 hipError_t launch_pool(Prof* prof, const float* u, int rows, int T, int S, float* p_out, float* s_out,
                        hipStream_t st);
 hipError_t launch_rank(const Workspace& ws, const float* s, int T, int32_t* rank_out, hipStream_t st);
+int rank_max_tiles();      // tiles (workgroups) one sort launch may have on this device
+int64_t rank_max_tokens(); // largest T one ranking call takes on this device
 // push != 0: first account for this layer's freshly written ring row in the state (a layer index
 // that does not follow state->last_layer restarts the ring)
 hipError_t launch_rankvar(const Workspace& ws, const int32_t* ring, int l_obs, int T, int layer_idx,

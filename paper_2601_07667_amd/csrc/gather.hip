@@ -8,7 +8,7 @@
 namespace asl {
 
 constexpr int kGatherThreads = 256;
-constexpr int kGatherUnroll = 4;      // pieces per thread, all loads in flight before the first store
+constexpr int kGatherUnroll = 4;      // pieces per thread (the kernel body is written out for four)
 
 // grid: x = blocks of kGatherThreads * kGatherUnroll pieces of one (head, tensor, layer) slab,
 //       y = KV head, z = layer * n_tensors + tensor (0 = K, 1 = V).
@@ -34,26 +34,34 @@ gather_kernel(GatherArgs a) {
   const int32_t* idx = a.idx + ((int64_t)layer * a.idx_rows + (a.idx_rows == 1 ? 0 : h)) * a.n_idx;
   const uint32_t total = (uint32_t)a.n_idx * (uint32_t)a.cpr;          // < 2^31, checked by the host
   const uint32_t q0 = blockIdx.x * (kGatherThreads * kGatherUnroll) + threadIdx.x;
-  uint32_t row[kGatherUnroll], c[kGatherUnroll];
-  int tok[kGatherUnroll];
-#pragma unroll
-  for (int u = 0; u < kGatherUnroll; ++u) {
-    const uint32_t q = q0 + u * kGatherThreads;
-    row[u] = POW2 ? (q >> a.cpr_shift) : (q / (uint32_t)a.cpr);
-    c[u] = POW2 ? (q & ((uint32_t)a.cpr - 1u)) : (q - row[u] * (uint32_t)a.cpr);
-    tok[u] = (q < total) ? idx[row[u]] : 0;
-  }
-  uint4 val[kGatherUnroll];
-#pragma unroll
-  for (int u = 0; u < kGatherUnroll; ++u) {
-    const uint32_t q = q0 + u * kGatherThreads;
-    if (q < total) val[u] = *reinterpret_cast<const uint4*>(src_base + (int64_t)tok[u] * stt + c[u] * 16);
-  }
-#pragma unroll
-  for (int u = 0; u < kGatherUnroll; ++u) {
-    const uint32_t q = q0 + u * kGatherThreads;
-    if (q < total) *reinterpret_cast<uint4*>(dst_base + (int64_t)q * 16) = val[u];
-  }
+  // The tensors are device (global) memory: say so, so that plain global loads and stores are used.
+  typedef const char __attribute__((address_space(1))) * GSrc;
+  typedef char __attribute__((address_space(1))) * GDst;
+  typedef uint32_t Piece __attribute__((ext_vector_type(4)));          // 16 bytes
+  typedef const Piece __attribute__((address_space(1))) * GSrc16;
+  typedef Piece __attribute__((address_space(1))) * GDst16;
+  typedef const int32_t __attribute__((address_space(1))) * GIdx;
+  const GSrc src = (GSrc)src_base;
+  const GDst dst = (GDst)dst_base;
+  const GIdx gi = (GIdx)idx;
+  // Loads are unconditional (piece numbers past the end are clamped to the last piece) so that all
+  // four index loads, then all four row loads, are in flight together; only the stores are
+  // predicated.  Written out rather than looped: the values must stay in registers.
+  const uint32_t last = total - 1u;
+  const uint32_t qa = q0, qb = q0 + kGatherThreads, qc = q0 + 2 * kGatherThreads, qd = q0 + 3 * kGatherThreads;
+  const uint32_t ca = min(qa, last), cb = min(qb, last), cc = min(qc, last), cd = min(qd, last);
+  const uint32_t cpr = (uint32_t)a.cpr;
+  const uint32_t ra = POW2 ? (ca >> a.cpr_shift) : (ca / cpr), rb = POW2 ? (cb >> a.cpr_shift) : (cb / cpr);
+  const uint32_t rc = POW2 ? (cc >> a.cpr_shift) : (cc / cpr), rd = POW2 ? (cd >> a.cpr_shift) : (cd / cpr);
+  const int ta = gi[ra], tb = gi[rb], tc = gi[rc], td = gi[rd];
+  const Piece va = *(GSrc16)(src + (int64_t)ta * stt + (int64_t)(ca - ra * cpr) * 16);
+  const Piece vb = *(GSrc16)(src + (int64_t)tb * stt + (int64_t)(cb - rb * cpr) * 16);
+  const Piece vc = *(GSrc16)(src + (int64_t)tc * stt + (int64_t)(cc - rc * cpr) * 16);
+  const Piece vd = *(GSrc16)(src + (int64_t)td * stt + (int64_t)(cd - rd * cpr) * 16);
+  if (qa < total) *(GDst16)(dst + (int64_t)qa * 16) = va;
+  if (qb < total) *(GDst16)(dst + (int64_t)qb * 16) = vb;
+  if (qc < total) *(GDst16)(dst + (int64_t)qc * 16) = vc;
+  if (qd < total) *(GDst16)(dst + (int64_t)qd * 16) = vd;
 }
 
 hipError_t launch_gather(Prof* prof, const GatherArgs& args, int Hk, int n_layers, hipStream_t st) {

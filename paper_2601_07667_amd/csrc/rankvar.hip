@@ -4,9 +4,9 @@
 // Ranks are a permutation, so "the k smallest ranks of a row" is rank < k and the union over rows
 // is  min_l R[l,t] < k.  Per token the population variance times n^2 is the integer
 // n * sum R^2 - (sum R)^2; the sum over the union is accumulated exactly in 64-bit integers
-// (per-workgroup partials; integer sums are order-independent); a second one-workgroup kernel adds
+// (per-workgroup partials; integer sums are order-independent); workgroup 0 of the same launch adds
 // the partials and performs the single double-precision division, the comparison with tau and the
-// state update.  No atomics, no fences.
+// state update.  No read-modify-write atomics, no fences.
 #include "asl_internal.h"
 
 namespace asl {
@@ -39,7 +39,7 @@ __global__ void stat_skip_kernel(asl_stat* out, asl_state* state, int layer_idx,
 }
 
 // Rows in use after (optionally) pushing this layer's row: a pure function of the old state, so
-// every workgroup derives it on its own; only the last workgroup writes the state back.
+// every workgroup derives it on its own; only workgroup 0 writes the state back.
 __device__ __forceinline__ int rows_in_use(const asl_state* state, int layer_idx, int l_obs, int push) {
   int n = state->n_valid_rows;
   if (push) {
@@ -49,15 +49,22 @@ __device__ __forceinline__ int rows_in_use(const asl_state* state, int layer_idx
   return n;
 }
 
-// Kernel 1: per-workgroup partial sums over the union (no atomics; integers, so the order of the
-// later addition does not matter).
+// Per-workgroup partial sums over the union (integers, so the order of the later addition does not
+// matter), handed to workgroup 0 through tagged words (see asl_internal.h: four words per
+// workgroup carry the 64-bit partial numerator in pieces of 28 bits and the partial union count).
+// Workgroup 0 waits for all of them, adds them up and performs the single division, the comparison
+// with tau and the state update; the other workgroups wait for nobody, so the launch needs no
+// particular residency.  Every workgroup reads the old state before it publishes, and workgroup 0
+// writes the state only after it has seen every publication.
 __global__ void __launch_bounds__(kVarThreads)
-rankvar_partial_kernel(const int32_t* __restrict__ ring, int l_obs, int T, int layer_idx, int k, int push,
-                       const asl_state* __restrict__ state, unsigned long long* __restrict__ part_num,
-                       uint32_t* __restrict__ part_cnt) {
+rankvar_kernel(const int32_t* __restrict__ ring, int l_obs, int T, int layer_idx, int k, double tau, int push,
+               asl_state* state, asl_stat* out, unsigned long long* __restrict__ table,
+               unsigned long long* __restrict__ epoch, uint32_t* __restrict__ fault) {
   __shared__ unsigned long long red_num[kVarThreads / 64];
   __shared__ uint32_t red_cnt[kVarThreads / 64];
+  __shared__ int gave_up;
   const int tid = threadIdx.x;
+  const unsigned long long tag = *epoch + 1ull;
   const int n = rows_in_use(state, layer_idx, l_obs, push);
   unsigned long long num = 0;
   uint32_t cnt = 0;
@@ -90,6 +97,7 @@ rankvar_partial_kernel(const int32_t* __restrict__ ring, int l_obs, int T, int l
     red_num[tid >> 6] = num;
     red_cnt[tid >> 6] = cnt;
   }
+  if (tid == 0) gave_up = 0;
   __syncthreads();
   if (tid == 0) {
     unsigned long long bn = 0;
@@ -98,25 +106,26 @@ rankvar_partial_kernel(const int32_t* __restrict__ ring, int l_obs, int T, int l
       bn += red_num[w];
       bc += red_cnt[w];
     }
-    part_num[blockIdx.x] = bn;
-    part_cnt[blockIdx.x] = bc;
+    unsigned long long* mine = table + (int64_t)blockIdx.x * 4;
+    const uint32_t m14 = (1u << kFlagCountBits) - 1u;
+    flag_publish(mine + 0, tag, (uint32_t)bn & m14, (uint32_t)(bn >> 14) & m14);
+    flag_publish(mine + 1, tag, (uint32_t)(bn >> 28) & m14, (uint32_t)(bn >> 42) & m14);
+    flag_publish(mine + 2, tag, (uint32_t)(bn >> 56) & m14, 0u);
+    flag_publish(mine + 3, tag, bc & m14, (bc >> 14) & m14);
   }
-}
+  if (blockIdx.x != 0) return;
 
-// Kernel 2 (one workgroup): add the partials, one division, the comparison with tau, state update.
-__global__ void __launch_bounds__(kVarThreads)
-rankvar_final_kernel(int n_parts, int l_obs, int layer_idx, double tau, int push, asl_state* state,
-                     asl_stat* out, const unsigned long long* __restrict__ part_num,
-                     const uint32_t* __restrict__ part_cnt) {
-  __shared__ unsigned long long red_num[kVarThreads / 64];
-  __shared__ uint32_t red_cnt[kVarThreads / 64];
-  const int tid = threadIdx.x;
-  const int n = rows_in_use(state, layer_idx, l_obs, push);
+  // workgroup 0: gather every workgroup's partials (thread b takes workgroups b, b + 256, ...)
+  __syncthreads();                                   // red_* are reused below
   unsigned long long total = 0;
   uint32_t m = 0;
-  for (int b = tid; b < n_parts; b += kVarThreads) {
-    total += part_num[b];
-    m += part_cnt[b];
+  for (int b = tid; b < (int)gridDim.x; b += kVarThreads) {
+    unsigned long long v[kFlagBatch];
+    if (!flag_poll_batch<1>(table + (int64_t)b * 4, 1, 0, 4, tag, v)) gave_up = 1;
+    const unsigned long long piece0 = (unsigned long long)flag_count0(v[0]) | ((unsigned long long)flag_count1(v[0]) << 14);
+    const unsigned long long piece1 = (unsigned long long)flag_count0(v[1]) | ((unsigned long long)flag_count1(v[1]) << 14);
+    total += piece0 | (piece1 << 28) | ((unsigned long long)flag_count0(v[2]) << 56);
+    m += flag_count0(v[3]) | (flag_count1(v[3]) << 14);
   }
   for (int o = 32; o > 0; o >>= 1) {
     total += __shfl_down(total, o);
@@ -128,6 +137,18 @@ rankvar_final_kernel(int n_parts, int l_obs, int layer_idx, double tau, int push
   }
   __syncthreads();                                   // every thread has read the old state by now
   if (tid != 0) return;
+  if (gave_up) {                                     // a peer never reported: no result, state untouched
+    *fault = 1u;
+    out->var_top = __builtin_nan("");
+    out->rel_var = __builtin_nan("");
+    out->numerator = 0;
+    out->union_size = 0;
+    out->n_rows = n;
+    out->evaluated = 0;
+    out->selected = 0;
+    return;
+  }
+  *epoch = tag;
   total = 0;
   m = 0;
   for (int w = 0; w < kVarThreads / 64; ++w) {
@@ -180,10 +201,8 @@ hipError_t launch_rankvar(const Workspace& ws, const int32_t* ring, int l_obs, i
                           int k, double tau, int push, asl_state* state, asl_stat* out, hipStream_t st) {
   int blocks = (T + kVarThreads - 1) / kVarThreads;
   if (blocks > kVarMaxBlocks) blocks = kVarMaxBlocks;
-  ASL_LAUNCH(ws.prof, kKernRankvar, st, rankvar_partial_kernel, dim3(blocks), dim3(kVarThreads), 0, st, ring,
-             l_obs, T, layer_idx, k, push, state, ws.var_part_num, ws.var_part_cnt);
-  ASL_LAUNCH(ws.prof, kKernRankvarFinal, st, rankvar_final_kernel, dim3(1), dim3(kVarThreads), 0, st, blocks, l_obs,
-             layer_idx, tau, push, state, out, ws.var_part_num, ws.var_part_cnt);
+  ASL_LAUNCH(ws.prof, kKernRankvar, st, rankvar_kernel, dim3(blocks), dim3(kVarThreads), 0, st, ring, l_obs, T,
+             layer_idx, k, tau, push, state, out, ws.var_table, ws.var_epoch, ws.fault);
   return hipGetLastError();
 }
 

@@ -2,18 +2,33 @@
 // ascending token order and followed by the window tokens (Alg. 1 steps 9-10 per KV head;
 // Alg. 2 steps 11-12 on the all-head scores).
 //
-// Radix select on the same order-preserving key transform as the rank kernel: four 8-bit
-// histogram passes from the most significant digit narrow down the k-th key, then an order-
-// preserving compaction keeps every key below the threshold key and the first k_rem keys equal
-// to it.  Integer work throughout: the result does not depend on scheduling.
+// Exact selection in three small launches that read the scores once and never wait for each other:
+//  1. guess    one workgroup per row looks at an evenly strided sample of the row and takes the
+//              sample's m-th smallest key (keys are an order-preserving transform of the scores,
+//              ascending key = descending score) as a bound that, with m a few standard deviations
+//              above the expected number of top-k members in the sample, admits at least k keys
+//              of the row and not many more;
+//  2. filter   one workgroup per tile of 4096 tokens keeps the tile's keys <= the bound, in token
+//              order, in the tile's own segment of a candidate buffer (no offsets to agree on);
+//  3. finish   one workgroup per row loads the row's candidates (a few thousand) into LDS, finds
+//              the k-th smallest key among them by radix select, and writes the kept tokens in
+//              order.
+// The bound is only a guess: if fewer than k keys passed it, or a tile's or the row's candidates
+// do not fit their buffers, step 3 runs the same selection over the whole row straight from the
+// scores instead (slower, same result).  The result therefore never depends on the sample.
+// Integer work throughout: nothing depends on scheduling.
 #include "asl_internal.h"
 
 namespace asl {
 
-constexpr int kSelThreads = 256;
+constexpr int kSelThreads = 256;                       // filter workgroup
 constexpr int kSelWaves = kSelThreads / 64;
 constexpr int kSelPerWave = kSelTile / kSelWaves;     // 1024
 constexpr int kSelRounds = kSelPerWave / 64;          // 16
+constexpr int kFinThreads = 1024;                      // guess / finish workgroup
+constexpr int kFinWaves = kFinThreads / 64;
+constexpr int kFinPerThread = 8;                       // consecutive elements per thread in the ordered write
+constexpr uint32_t kSegOverflow = 0xffffffffu;         // a tile's count when its segment was too small
 
 __device__ __forceinline__ uint32_t sel_key(float f) {
   if (f == 0.0f) f = 0.0f;
@@ -22,218 +37,319 @@ __device__ __forceinline__ uint32_t sel_key(float f) {
   return ~asc;                                        // ascending key == descending score
 }
 
-// Workspace layout (all plain stores, no atomics):
-//   hist[pass][row][tile][256]  digit histogram of the keys of that tile whose higher digits match
-//                               the prefix chosen so far
-//   state[pass][row][2]         {prefix of `pass` digits, keys still to take} as known BEFORE pass
-//   tile_lt[row][tile]          keys of the tile already known to lie below the threshold key
-// Every workgroup of pass p+1 re-derives the digit chosen from the pass-p histograms (a few tens
-// of KB of L2 reads), so nothing has to be serialised through atomics or a last workgroup.
+// Sample size for a row of T keys and the rank m of the sample key taken as the bound:
+// f = n_s / T of the row is sampled, the top-k members among the sample are ~Binomial(n_s, k / T)
+// with mean k f; m = k f + 5 sqrt(k f) + 4 leaves the bound too low with probability < 1e-6.
+__host__ __device__ inline int sel_sample_size(int T) {
+  int n = T / 32;
+  n = n < 1024 ? 1024 : n;
+  n = n > kSelMaxSample ? kSelMaxSample : n;
+  return n < T ? n : T;
+}
+__host__ __device__ inline int sel_sample_rank(int T, int k, int n_s) {
+  const float kf = (float)k * (float)n_s / (float)T;
+  const int m = (int)(kf + 5.0f * sqrtf(kf) + 4.0f);
+  return m;                                            // >= n_s means: no usable bound, admit everything
+}
 
-struct Pick {
-  uint32_t digit;      // digit of the k-th key in this pass
-  uint32_t k_rem;      // keys still to take among those equal to the prefix incl. this digit
-  uint32_t lt_mine;    // this tile's keys with a smaller digit
-  uint32_t lt_prev;    // earlier tiles' keys with a smaller digit
-  uint32_t eq_prev;    // earlier tiles' keys with exactly this digit
-};
-
-// hp = hist of one (pass,row): [n_tiles][256].  All 256 threads take part.
-__device__ __forceinline__ Pick pick_digit(const uint32_t* __restrict__ hp, int n_tiles, int me,
-                                           uint32_t k_rem_in, uint32_t* sm /* >= 16 words */) {
+// Exclusive prefix over the workgroup's threads of two counters (kFinThreads threads), plus totals.
+__device__ __forceinline__ void block_scan2(uint32_t a, uint32_t b, uint32_t* sm /* 2*kFinWaves+2 */,
+                                            uint32_t& a_excl, uint32_t& b_excl, uint32_t& a_tot, uint32_t& b_tot) {
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-  // column `tid` of the [n_tiles][256] table: all tiles, and the tiles before this one.
-  // Loads are independent; unrolled so that many are in flight at once.
-  uint32_t tot = 0, prev = 0;
-  const uint32_t mine = hp[(int64_t)me * 256 + tid];
-  int t = 0;
-  for (; t + 16 <= n_tiles; t += 16) {
-    uint32_t v[16];
-#pragma unroll
-    for (int u = 0; u < 16; ++u) v[u] = hp[(int64_t)(t + u) * 256 + tid];
-#pragma unroll
-    for (int u = 0; u < 16; ++u) {
-      tot += v[u];
-      prev += (t + u < me) ? v[u] : 0u;
-    }
-  }
-  for (; t < n_tiles; ++t) {
-    const uint32_t v = hp[(int64_t)t * 256 + tid];
-    tot += v;
-    prev += (t < me) ? v : 0u;
-  }
-  uint32_t incl = tot;
+  uint32_t ai = a, bi = b;
 #pragma unroll
   for (int o = 1; o < 64; o <<= 1) {
-    const uint32_t up = __shfl_up(incl, o);
-    if (lane >= o) incl += up;
-  }
-  __syncthreads();                                     // sm may still be in use by a previous call
-  if (lane == 63) sm[wave] = incl;
-  if (tid == 0) {                                      // defined result even if no digit qualifies
-    sm[4] = 0;                                         // (cannot happen while k <= T)
-    sm[5] = 0;
-    sm[14] = 0;
-  }
-  __syncthreads();
-  uint32_t excl = incl - tot;
-  for (int w = 0; w < wave; ++w) excl += sm[w];
-  if (excl < k_rem_in && excl + tot >= k_rem_in) {     // exactly one digit satisfies this
-    sm[4] = (uint32_t)tid;
-    sm[5] = k_rem_in - excl;
-    sm[14] = prev;                                     // earlier tiles' keys with exactly this digit
-  }
-  __syncthreads();
-  Pick p;
-  p.digit = sm[4];
-  p.k_rem = sm[5];
-  p.eq_prev = sm[14];
-  uint32_t a = ((uint32_t)tid < p.digit) ? mine : 0u;
-  uint32_t b = ((uint32_t)tid < p.digit) ? prev : 0u;
-  for (int o = 32; o > 0; o >>= 1) {
-    a += __shfl_down(a, o);
-    b += __shfl_down(b, o);
-  }
-  if (lane == 0) {
-    sm[6 + wave] = a;
-    sm[10 + wave] = b;
-  }
-  __syncthreads();
-  p.lt_mine = sm[6] + sm[7] + sm[8] + sm[9];
-  p.lt_prev = sm[10] + sm[11] + sm[12] + sm[13];
-  return p;
-}
-
-// Histogram pass `pass` (0..3, most significant digit first).
-__global__ void __launch_bounds__(kSelThreads)
-select_hist_kernel(const float* __restrict__ scores, int T, int n_tiles, int rows, int pass, int k,
-                   uint32_t* __restrict__ hist, uint32_t* __restrict__ state,
-                   uint32_t* __restrict__ tile_lt) {
-  __shared__ uint32_t h[kHistWords];
-  __shared__ uint32_t sm[16];
-  const int tid = threadIdx.x, row = blockIdx.y, tile = blockIdx.x;
-  const int shift = 24 - 8 * pass;
-  const float* sr = scores + (int64_t)row * T;
-  const int base = tile * kSelTile;
-  constexpr int E = kSelTile / kSelThreads;
-  uint32_t key[E];
-#pragma unroll
-  for (int i = 0; i < E; ++i) {                        // all loads in flight before the first use
-    const int e = base + i * kSelThreads + tid;
-    key[i] = (e < T) ? sel_key(sr[e]) : 0u;
-  }
-  uint32_t prefix = 0;
-  if (pass > 0) {
-    const uint32_t* st_in = state + ((int64_t)(pass - 1) * rows + row) * 2;
-    const uint32_t prefix_in = (pass == 1) ? 0u : st_in[0];
-    const uint32_t k_rem_in = (pass == 1) ? (uint32_t)k : st_in[1];
-    const uint32_t* hp = hist + ((int64_t)(pass - 1) * rows + row) * n_tiles * 256;
-    const Pick p = pick_digit(hp, n_tiles, tile, k_rem_in, sm);
-    prefix = (prefix_in << 8) | p.digit;
-    if (tid == 0) {
-      uint32_t* lt = tile_lt + (int64_t)row * n_tiles + tile;
-      *lt = (pass == 1 ? 0u : *lt) + p.lt_mine;
-      if (tile == 0) {
-        uint32_t* st_out = state + ((int64_t)pass * rows + row) * 2;
-        st_out[0] = prefix;
-        st_out[1] = p.k_rem;
-      }
+    const uint32_t ua = __shfl_up(ai, o), ub = __shfl_up(bi, o);
+    if (lane >= o) {
+      ai += ua;
+      bi += ub;
     }
   }
-  hist_clear(h, tid, kSelThreads);
-  __syncthreads();
-#pragma unroll
-  for (int i = 0; i < E; ++i) {
-    const int e = base + i * kSelThreads + tid;
-    const bool match = (pass == 0) || ((key[i] >> (shift + 8)) == prefix);
-    if (e < T && match) hist_add(h, tid, (key[i] >> shift) & 255u);
+  __syncthreads();                                     // sm may still be in use
+  if (lane == 63) {
+    sm[wave] = ai;
+    sm[kFinWaves + wave] = bi;
   }
   __syncthreads();
-  hist[(((int64_t)pass * rows + row) * n_tiles + tile) * 256 + tid] = hist_total(h, tid);
+  uint32_t ab = 0, bb = 0, at = 0, bt = 0;
+  for (int w = 0; w < kFinWaves; ++w) {
+    const uint32_t x = sm[w], y = sm[kFinWaves + w];
+    ab += (w < wave) ? x : 0u;
+    bb += (w < wave) ? y : 0u;
+    at += x;
+    bt += y;
+  }
+  a_excl = ab + ai - a;
+  b_excl = bb + bi - b;
+  a_tot = at;
+  b_tot = bt;
 }
 
-// Ordered compaction: position of a kept token = (#below before it) + min(#equal before it, k_rem).
-__global__ void __launch_bounds__(kSelThreads)
-select_write_kernel(const float* __restrict__ scores, int T, int n_tiles, int rows, int k, int W,
-                    const uint32_t* __restrict__ hist, const uint32_t* __restrict__ state,
-                    const uint32_t* __restrict__ tile_lt, int32_t* __restrict__ idx_out) {
-  __shared__ uint32_t sm[16];
-  __shared__ uint32_t red[kSelWaves];
-  __shared__ uint32_t wave_tot[2][kSelWaves];
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, row = blockIdx.y, tile = blockIdx.x;
+// Radix select over n keys read through `key_at(i)`: returns the k-th smallest key (1 <= k <= n)
+// and how many of the keys equal to it belong to the k smallest (k_rem >= 1).  All kFinThreads
+// threads take part.  The keys' common leading bits are skipped: digits are taken from
+// key - min over the bits in which min and max differ, so the first digit already spreads the keys
+// over the bins (scores of one row share their sign and most of their exponent).
+// h: kHistWords-word LDS histogram (bank-staggered copies), sm: >= 2 * kFinWaves + 2 words.
+template <typename KeyAt>
+__device__ __forceinline__ void radix_select_block(int n, uint32_t k, KeyAt key_at, uint32_t* h, uint32_t* sm,
+                                                   uint32_t& thr_out, uint32_t& k_rem_out) {
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  uint32_t lo = 0xffffffffu, hi = 0u;
+  for (int i = tid; i < n; i += kFinThreads) {
+    const uint32_t key = key_at(i);
+    lo = key < lo ? key : lo;
+    hi = key > hi ? key : hi;
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    const uint32_t l2 = __shfl_xor(lo, o), h2 = __shfl_xor(hi, o);
+    lo = l2 < lo ? l2 : lo;
+    hi = h2 > hi ? h2 : hi;
+  }
+  __syncthreads();                                     // sm may still be in use
+  if (lane == 0) {
+    sm[wave] = lo;
+    sm[kFinWaves + wave] = hi;
+  }
+  __syncthreads();
+  for (int w = 0; w < kFinWaves; ++w) {
+    const uint32_t l2 = sm[w], h2 = sm[kFinWaves + w];
+    lo = l2 < lo ? l2 : lo;
+    hi = h2 > hi ? h2 : hi;
+  }
+  const uint32_t span = hi - lo;
+  const int bits = span == 0 ? 0 : 32 - __clz((int)span);
+  const int n_pass = (bits + 7) / 8;                   // uniform; 0 when all keys are equal
+  uint32_t prefix = 0, k_rem = k;
+  for (int pass = 0; pass < n_pass; ++pass) {
+    const int shift = 8 * (n_pass - 1 - pass);
+    __syncthreads();                                   // h and sm of the previous pass are consumed
+    hist_clear(h, tid, kFinThreads);
+    __syncthreads();
+    for (int i = tid; i < n; i += kFinThreads) {
+      const uint32_t v = key_at(i) - lo;
+      if (pass == 0 || (v >> (shift + 8)) == prefix) hist_add(h, tid, (v >> shift) & 255u);
+    }
+    __syncthreads();
+    // exclusive scan of the 256 counts by the first four wavefronts; the digit d with
+    // excl < k_rem <= excl + count holds the k-th key
+    uint32_t cnt = 0, incl = 0;
+    if (tid < 256) {
+      cnt = hist_total(h, tid);
+      incl = cnt;
+#pragma unroll
+      for (int o = 1; o < 64; o <<= 1) {
+        const uint32_t up = __shfl_up(incl, o);
+        if (lane >= o) incl += up;
+      }
+      if (lane == 63) sm[wave] = incl;
+    }
+    if (tid == 0) {
+      sm[4] = 0;                                       // defined even if no digit qualifies
+      sm[5] = 1;                                       // (cannot happen while 1 <= k <= n)
+    }
+    __syncthreads();
+    if (tid < 256) {
+      uint32_t excl = incl - cnt;
+      for (int w = 0; w < wave; ++w) excl += sm[w];
+      if (excl < k_rem && excl + cnt >= k_rem) {       // exactly one digit satisfies this
+        sm[4] = (uint32_t)tid;
+        sm[5] = k_rem - excl;
+      }
+    }
+    __syncthreads();
+    prefix = (prefix << 8) | sm[4];
+    k_rem = sm[5];
+  }
+  thr_out = lo + prefix;
+  k_rem_out = k_rem;
+}
+
+// Step 1: bound[row] = the m-th smallest key of the row's strided sample (0xffffffff: admit all).
+__global__ void __launch_bounds__(kFinThreads)
+select_guess_kernel(const float* __restrict__ scores, int T, int row0, int k, uint32_t* __restrict__ bound) {
+  __shared__ uint32_t samp[kSelMaxSample];
+  __shared__ uint32_t h[kHistWords];
+  __shared__ uint32_t sm[2 * kFinWaves + 2];
+  const int row = row0 + blockIdx.x, tid = threadIdx.x;
+  const int n_s = sel_sample_size(T);
+  const int m = sel_sample_rank(T, k, n_s);
+  if (m >= n_s) {                                      // uniform
+    if (tid == 0) bound[row] = 0xffffffffu;
+    return;
+  }
   const float* sr = scores + (int64_t)row * T;
-  // this wave's keys (kSelPerWave consecutive tokens, 64 per round), loaded before anything waits
+  for (int j = tid; j < n_s; j += kFinThreads)
+    samp[j] = sel_key(sr[(int)(((int64_t)j * T) / n_s)]);      // strictly increasing positions
+  uint32_t thr, k_rem;
+  radix_select_block(n_s, (uint32_t)m, [&](int i) { return samp[i]; }, h, sm, thr, k_rem);
+  if (tid == 0) bound[row] = thr;
+}
+
+// Step 2: the tile's keys <= bound, in token order, to the tile's segment of the candidate buffer.
+//   cand_key / cand_idx [rows][n_tiles][kSelSegment], seg_count [rows][n_tiles]
+__global__ void __launch_bounds__(kSelThreads)
+select_filter_kernel(const float* __restrict__ scores, int T, int n_tiles, int row0,
+                     const uint32_t* __restrict__ bound, uint32_t* __restrict__ cand_key,
+                     uint32_t* __restrict__ cand_idx, uint32_t* __restrict__ seg_count) {
+  __shared__ uint32_t wave_tot[kSelWaves];
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, tile = blockIdx.x;
+  const int row = row0 + blockIdx.y;
+  const float* sr = scores + (int64_t)row * T;
   const int base = tile * kSelTile + wave * kSelPerWave;
   uint32_t key[kSelRounds];
 #pragma unroll
-  for (int r = 0; r < kSelRounds; ++r) {
+  for (int r = 0; r < kSelRounds; ++r) {               // all loads in flight before the first use
     const int e = base + r * 64 + lane;
-    key[r] = (e < T) ? sel_key(sr[e]) : 0xffffffffu;
+    key[r] = (e < T) ? sel_key(sr[e]) : 0u;
   }
-  const uint32_t* st_in = state + ((int64_t)3 * rows + row) * 2;          // 3-digit prefix, written by pass 3
-  const uint32_t* h3 = hist + ((int64_t)3 * rows + row) * n_tiles * 256;
-  const Pick p = pick_digit(h3, n_tiles, tile, st_in[1], sm);
-  const uint32_t thr = (st_in[0] << 8) | p.digit;
-  const uint32_t k_rem = p.k_rem;
-  int32_t* out = idx_out + (int64_t)row * (k + W);
-
-  // keys below the threshold in the tiles before this one (passes 0-2 from tile_lt, pass 3 from h3)
-  uint32_t lt_b = 0;
-  for (int t = tid; t < tile; t += kSelThreads) lt_b += tile_lt[(int64_t)row * n_tiles + t];
-  for (int o = 32; o > 0; o >>= 1) lt_b += __shfl_down(lt_b, o);
-  if (lane == 0) red[wave] = lt_b;
-
-  // this wave's totals
-  uint32_t w_lt = 0, w_eq = 0;
+  const uint32_t b = bound[row];
+  uint32_t w_cnt = 0;
 #pragma unroll
   for (int r = 0; r < kSelRounds; ++r) {
-    const int e = base + r * 64 + lane;
-    const bool v = e < T;
-    w_lt += __popcll(__ballot(v && key[r] < thr));
-    w_eq += __popcll(__ballot(v && key[r] == thr));
+    const bool keep = (base + r * 64 + lane < T) && key[r] <= b;
+    w_cnt += __popcll(__ballot(keep));
   }
-  if (lane == 0) {
-    wave_tot[0][wave] = w_lt;
-    wave_tot[1][wave] = w_eq;
-  }
+  if (lane == 0) wave_tot[wave] = w_cnt;
   __syncthreads();
-  uint32_t lt_run = p.lt_prev, eq_run = p.eq_prev;
-  for (int w = 0; w < kSelWaves; ++w) lt_run += red[w];
-  for (int w = 0; w < wave; ++w) {
-    lt_run += wave_tot[0][w];
-    eq_run += wave_tot[1][w];
+  uint32_t run = 0, total = 0;
+  for (int w = 0; w < kSelWaves; ++w) {
+    run += (w < wave) ? wave_tot[w] : 0u;
+    total += wave_tot[w];
   }
+  const int64_t seg = ((int64_t)row * n_tiles + tile);
+  if (tid == 0) seg_count[seg] = (total > (uint32_t)kSelSegment) ? kSegOverflow : total;
+  if (total > (uint32_t)kSelSegment) return;           // uniform: the finish step takes the whole row instead
+  uint32_t* ck = cand_key + seg * kSelSegment;
+  uint32_t* ci = cand_idx + seg * kSelSegment;
   const uint64_t lt_mask = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
 #pragma unroll
   for (int r = 0; r < kSelRounds; ++r) {
     const int e = base + r * 64 + lane;
-    const bool v = e < T;
-    const bool is_lt = v && key[r] < thr;
-    const bool is_eq = v && key[r] == thr;
-    const uint64_t b_lt = __ballot(is_lt), b_eq = __ballot(is_eq);
-    const uint32_t lt_before = lt_run + (uint32_t)__popcll(b_lt & lt_mask);
-    const uint32_t eq_before = eq_run + (uint32_t)__popcll(b_eq & lt_mask);
-    if (is_lt || (is_eq && eq_before < k_rem)) {
-      const uint32_t pos = lt_before + (eq_before < k_rem ? eq_before : k_rem);
-      if (pos < (uint32_t)k) out[pos] = e;             // always true for consistent counts
+    const bool keep = (e < T) && key[r] <= b;
+    const uint64_t bal = __ballot(keep);
+    if (keep) {
+      const uint32_t pos = run + (uint32_t)__popcll(bal & lt_mask);
+      ck[pos] = key[r];
+      ci[pos] = (uint32_t)e;
     }
-    lt_run += (uint32_t)__popcll(b_lt);
-    eq_run += (uint32_t)__popcll(b_eq);
+    run += (uint32_t)__popcll(bal);
+  }
+}
+
+// Ordered write of the kept elements of a sequence of n (key, token) pairs given in token order:
+// kept = key < thr, or key == thr and fewer than k_rem equal keys precede it.
+template <typename KeyAt, typename TokAt>
+__device__ __forceinline__ void ordered_write(int n, uint32_t thr, uint32_t k_rem, int k, KeyAt key_at, TokAt tok_at,
+                                              uint32_t* sm, int32_t* __restrict__ out) {
+  const int tid = threadIdx.x;
+  uint32_t lt_base = 0, eq_base = 0;
+  for (int c0 = 0; c0 < n; c0 += kFinThreads * kFinPerThread) {
+    const int i0 = c0 + tid * kFinPerThread;
+    uint32_t key[kFinPerThread];
+    uint32_t lt = 0, eq = 0;
+#pragma unroll
+    for (int j = 0; j < kFinPerThread; ++j) {
+      key[j] = (i0 + j < n) ? key_at(i0 + j) : 0xffffffffu;
+      lt += (i0 + j < n && key[j] < thr) ? 1u : 0u;
+      eq += (i0 + j < n && key[j] == thr) ? 1u : 0u;
+    }
+    uint32_t lt_excl, eq_excl, lt_tot, eq_tot;
+    block_scan2(lt, eq, sm, lt_excl, eq_excl, lt_tot, eq_tot);
+    uint32_t lt_run = lt_base + lt_excl, eq_run = eq_base + eq_excl;
+#pragma unroll
+    for (int j = 0; j < kFinPerThread; ++j) {
+      if (i0 + j < n) {
+        const bool is_lt = key[j] < thr, is_eq = key[j] == thr;
+        if (is_lt || (is_eq && eq_run < k_rem)) {
+          const uint32_t pos = lt_run + (eq_run < k_rem ? eq_run : k_rem);
+          if (pos < (uint32_t)k) out[pos] = (int32_t)tok_at(i0 + j);      // always true for consistent counts
+        }
+        lt_run += is_lt ? 1u : 0u;
+        eq_run += is_eq ? 1u : 0u;
+      }
+    }
+    lt_base += lt_tot;
+    eq_base += eq_tot;
+  }
+}
+
+// Step 3: one workgroup per row.  Dynamic LDS: kSelCandCap keys followed by kSelCandCap tokens.
+__global__ void __launch_bounds__(kFinThreads)
+select_finish_kernel(const float* __restrict__ scores, int T, int n_tiles, int row0, int k, int W,
+                     const uint32_t* __restrict__ cand_key, const uint32_t* __restrict__ cand_idx,
+                     const uint32_t* __restrict__ seg_count, int32_t* __restrict__ idx_out) {
+  extern __shared__ uint32_t lds_cand[];
+  __shared__ uint32_t h[kHistWords];
+  __shared__ uint32_t sm[2 * kFinWaves + 2];
+  __shared__ uint32_t seg_off[kSelMaxRowTiles + 1];
+  __shared__ int whole_row;
+  const int row = row0 + blockIdx.x, tid = threadIdx.x;
+  int32_t* out = idx_out + (int64_t)row * (k + W);
+  // offsets of the tiles' candidates in the row's candidate sequence: thread t takes tile t
+  {
+    uint32_t c = 0, over = 0;
+    if (tid < n_tiles && n_tiles <= kSelMaxRowTiles) {
+      c = seg_count[(int64_t)row * n_tiles + tid];
+      over = (c == kSegOverflow) ? 1u : 0u;
+      c = over ? 0u : c;
+    }
+    uint32_t c_excl, o_excl, c_tot, o_tot;
+    block_scan2(c, over, sm, c_excl, o_excl, c_tot, o_tot);
+    if (tid < n_tiles && n_tiles <= kSelMaxRowTiles) seg_off[tid] = c_excl;
+    if (tid == 0) {
+      if (n_tiles <= kSelMaxRowTiles) seg_off[n_tiles] = c_tot;
+      whole_row = (n_tiles > kSelMaxRowTiles || o_tot != 0 || c_tot < (uint32_t)k || c_tot > (uint32_t)kSelCandCap) ? 1 : 0;
+    }
+  }
+  __syncthreads();
+  uint32_t thr, k_rem;
+  if (!whole_row) {                                    // uniform
+    uint32_t* lk = lds_cand;
+    uint32_t* li = lds_cand + kSelCandCap;
+    const int n = (int)seg_off[n_tiles];
+    // wavefront w copies tiles w, w + kFinWaves, ...
+    for (int t = tid >> 6; t < n_tiles; t += kFinWaves) {
+      const uint32_t o = seg_off[t], c = seg_off[t + 1] - o;
+      const int64_t seg = ((int64_t)row * n_tiles + t) * kSelSegment;
+      for (uint32_t j = tid & 63; j < c; j += 64) {
+        lk[o + j] = cand_key[seg + j];
+        li[o + j] = cand_idx[seg + j];
+      }
+    }
+    __syncthreads();
+    radix_select_block(n, (uint32_t)k, [&](int i) { return lk[i]; }, h, sm, thr, k_rem);
+    ordered_write(n, thr, k_rem, k, [&](int i) { return lk[i]; }, [&](int i) { return li[i]; }, sm, out);
+  } else {
+    const float* sr = scores + (int64_t)row * T;
+    radix_select_block(T, (uint32_t)k, [&](int i) { return sel_key(sr[i]); }, h, sm, thr, k_rem);
+    ordered_write(T, thr, k_rem, k, [&](int i) { return sel_key(sr[i]); }, [&](int i) { return (uint32_t)i; }, sm, out);
   }
   // window tokens T .. T+W-1 (Alg. 1 step 10: Concat with I_w)
-  if (tile == 0)
-    for (int i = tid; i < W; i += kSelThreads) out[k + i] = T + i;
+  for (int i = tid; i < W; i += kFinThreads) out[k + i] = T + i;
 }
 
 hipError_t launch_select(const Workspace& ws, const float* scores, int rows, int T, int k, int W,
                          int32_t* idx_out, hipStream_t st) {
+  static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(select_finish_kernel),
+                                                     hipFuncAttributeMaxDynamicSharedMemorySize,
+                                                     2 * kSelCandCap * (int)sizeof(uint32_t));
+  if (attr != hipSuccess) return attr;
   const int n_tiles = (T + kSelTile - 1) / kSelTile;
-  const dim3 grid(n_tiles, rows), block(kSelThreads);
-  for (int pass = 0; pass < 4; ++pass)
-    ASL_LAUNCH(ws.prof, kKernSelHist, st, select_hist_kernel, grid, block, 0, st, scores, T, n_tiles, rows,
-               pass, k, ws.sel_hist, ws.sel_state, ws.sel_tile_cnt);
-  ASL_LAUNCH(ws.prof, kKernSelWrite, st, select_write_kernel, grid, block, 0, st, scores, T, n_tiles, rows, k,
-             W, ws.sel_hist, ws.sel_state, ws.sel_tile_cnt, idx_out);
+  // rows beyond what the candidate buffers hold at once take further rounds of the three launches
+  const int rows_per_round = ws.sel_rows;
+  for (int row0 = 0; row0 < rows; row0 += rows_per_round) {
+    const int nr = rows - row0 < rows_per_round ? rows - row0 : rows_per_round;
+    const float* sc = scores + (int64_t)row0 * T;
+    int32_t* io = idx_out + (int64_t)row0 * (k + W);
+    ASL_LAUNCH(ws.prof, kKernSelHist, st, select_guess_kernel, dim3(nr), dim3(kFinThreads), 0, st, sc, T, 0, k, ws.sel_bound);
+    ASL_LAUNCH(ws.prof, kKernSelHist, st, select_filter_kernel, dim3(n_tiles, nr), dim3(kSelThreads), 0, st, sc, T, n_tiles,
+               0, ws.sel_bound, ws.sel_cand_key, ws.sel_cand_idx, ws.sel_seg_count);
+    ASL_LAUNCH(ws.prof, kKernSelWrite, st, select_finish_kernel, dim3(nr), dim3(kFinThreads),
+               2 * kSelCandCap * sizeof(uint32_t), st, sc, T, n_tiles, 0, k, W, ws.sel_cand_key, ws.sel_cand_idx,
+               ws.sel_seg_count, io);
+  }
   return hipGetLastError();
 }
 

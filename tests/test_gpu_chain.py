@@ -63,6 +63,7 @@ def _pipeline(dev, L, layer_idx=0, ctx=None, state=None, ring=None, l_min=None, 
                I_all=I_all.cpu().numpy().astype(np.int64)[0], Kc=Kc.float().cpu().numpy(),
                Vc=Vc.float().cpu().numpy(), Ks=Ks.float().cpu().numpy(), Vs=Vs.float().cpu().numpy(),
                ring=ring, state=state)
+    assert ctx.asl_device_fault() == 0, "a workgroup gave up waiting for its peers"
     if own:
         ctx.close()
     return out

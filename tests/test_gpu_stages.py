@@ -17,6 +17,7 @@ pytestmark = pytest.mark.gpu
 def ctx(gpu_device):
     c = asl.Asl(262144, 8, 32 * 64)
     yield c
+    assert c.asl_device_fault() == 0, "a workgroup gave up waiting for its peers during this module"
     c.close()
 
 
