@@ -362,35 +362,51 @@ score_rowstats_kernel(const __bf16* __restrict__ q_obs, const __bf16* __restrict
   }
 }
 
-// Fold the per-chunk partials of every row into one log2-domain offset  m + log2(Z).
-// One wavefront per row: lanes stride over the chunks, then a fixed-order butterfly.
-// lse_out (optional): the same quantity as a natural logarithm, the rows' log-sum-exp.
+// Fold the per-chunk partials (m_c, z_c) of one query row into the row's log2-domain softmax offset
+// m + log2(Z).  Two lanes share a row (`half` = 0 or 1, partner = lane ^ 32): each takes every
+// second chunk, in chunk order with a running maximum; the two halves are added in a fixed order,
+// so every caller gets the same bits for the same partials.
+// p points at the row's partial of chunk 0; consecutive chunks are M float2 apart.
+__device__ __forceinline__ float combine_row(const float2* __restrict__ p, int M, int n_chunks, int half) {
+  // batches of kB chunks per lane: all loads of a batch are issued before the first is used
+  constexpr int kB = 48;
+  float m = kNegBig, z = 0.f;
+  for (int c0 = half; c0 < n_chunks; c0 += 2 * kB) {
+    float2 v[kB];
+#pragma unroll
+    for (int j = 0; j < kB; ++j) {
+      const int c = c0 + 2 * j;
+      v[j] = p[(int64_t)min(c, n_chunks - 1) * M];
+      if (c >= n_chunks) v[j] = make_float2(kNegBig, 0.f);
+    }
+    float mb = m;
+#pragma unroll
+    for (int j = 0; j < kB; ++j) mb = fmaxf(mb, v[j].x);
+    float zb = 0.f;
+#pragma unroll
+    for (int j = 0; j < kB; ++j) zb += v[j].y * fast_exp2(v[j].x - mb);
+    z = z * fast_exp2(m - mb) + zb;
+    m = mb;
+  }
+  const float mo = __shfl_xor(m, 32), zo = __shfl_xor(z, 32);
+  const float mm = fmaxf(m, mo);
+  const float za = z * fast_exp2(m - mm), zb2 = zo * fast_exp2(mo - mm);
+  const float zs = (half == 0) ? (za + zb2) : (zb2 + za);
+  return mm + log2f(zs);
+}
+
+// The offsets of all Hk*M rows (one wavefront per 32 rows), for callers that want the rows'
+// log-sum-exp: row_const[r] = m + log2(Z) and, as a natural logarithm, lse_out[r].
 __global__ void __launch_bounds__(256)
 score_combine_kernel(const float* __restrict__ row_part, int Hk, int M, int n_chunks,
                      float* __restrict__ row_const, float* __restrict__ lse_out) {
-  const int lane = threadIdx.x & 63;
-  const int r = blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (r >= Hk * M) return;
-  const int g = r / M, row = r % M;
+  const int lane = threadIdx.x & 63, ln = lane & 31, half = lane >> 5;
+  const int r = (blockIdx.x * 4 + (threadIdx.x >> 6)) * 32 + ln;
+  const int rr = min(r, Hk * M - 1);
+  const int g = rr / M, row = rr % M;
   const float2* p = reinterpret_cast<const float2*>(row_part) + (int64_t)g * n_chunks * M + row;
-  float m = kNegBig, z = 0.f;
-  for (int c = lane; c < n_chunks; c += 64) {
-    const float2 v = p[(int64_t)c * M];
-    const float mn = fmaxf(m, v.x);
-    z = z * exp2f(m - mn) + v.y * exp2f(v.x - mn);
-    m = mn;
-  }
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) {
-    const float mo = __shfl_xor(m, o), zo = __shfl_xor(z, o);
-    const float mn = fmaxf(m, mo);
-    // add the two partial sums in lane order so both partners compute the same bits
-    const float za = z * exp2f(m - mn), zb = zo * exp2f(mo - mn);
-    z = (lane & o) ? (zb + za) : (za + zb);
-    m = mn;
-  }
-  if (lane == 0) {
-    const float c = m + log2f(z);
+  const float c = combine_row(p, M, n_chunks, half);
+  if (half == 0 && r < Hk * M) {
     row_const[r] = c;
     if (lse_out != nullptr) lse_out[r] = c * kLn2;
   }
@@ -435,7 +451,8 @@ template <int D, int NW, int RB>
 __global__ void __launch_bounds__(NW * 64)
 score_colsum_kernel(const __bf16* __restrict__ q_obs, const __bf16* __restrict__ k, int64_t ksh,
                     int64_t kst, int Hk, int M, int N, int T, int n_cu, float c1,
-                    const float* __restrict__ row_const, float rc_mul, float* __restrict__ u_group) {
+                    const float* __restrict__ row_const, float rc_mul, const float* __restrict__ row_part,
+                    int n_parts, float* __restrict__ u_group) {
   constexpr int NT = loader_threads<D, NW>();      // threads that load the K tiles
   constexpr int NTHREADS = NW * 64;
   constexpr int KS = D / 16;
@@ -452,25 +469,38 @@ score_colsum_kernel(const __bf16* __restrict__ q_obs, const __bf16* __restrict__
   const int tile0 = cr.tile0, tile_end = cr.tile_end;
 
   ASL_LOAD_Q_FRAGS();
-  float rc[RB][16];
-#pragma unroll
-  for (int rb = 0; rb < RB; ++rb)
-#pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      const int row = row0 + rb * 32 + acc_row(r, half);
-      const float v = row_const[(int64_t)g * M + min(row, M - 1)] * rc_mul;
-      rc[rb][r] = (row < M) ? v : INFINITY;              // padded rows add 2^-inf = 0
-    }
   TilePieces<D, NT> tp;
   tp.init(kst, tid);
   // The chunk is walked from its last tile to its first: pass 1 walked it first to last, so the
   // tiles read most recently (still in the last-level cache) are the ones this pass reads first.
   const int n_my = max(tile_end - tile0, 0);
-  // prologue: STAGES-1 tiles in flight (after the loads above, so the in-order wait counts line up)
+  // prologue: STAGES-1 tiles in flight before the row offsets are worked out, so that their latency
+  // hides behind the first tiles' (later loads complete later: the counted waits below stay valid)
 #pragma unroll
   for (int j = 0; j < STAGES - 1; ++j)
     if (j < n_my) issue_tile_loads<D, NT>(tp, kg, kst, (tile_end - 1 - j) * KT, N, lds_k + j * TILE_ELEMS, tid);
 
+  // Log2-domain softmax offsets of this lane's accumulator rows: from the caller's log-sum-exp
+  // (row_const, scaled by rc_mul), or folded here from pass 1's per-chunk partials (row_part).
+  float rc[RB][16];
+#pragma unroll
+  for (int rb = 0; rb < RB; ++rb) {
+    float mine = 0.f;                                   // offset of row  row0 + 32*rb + ln
+    if (row_part != nullptr) {
+      const int qr = min(row0 + rb * 32 + ln, M - 1);
+      mine = combine_row(reinterpret_cast<const float2*>(row_part) + (int64_t)g * n_parts * M + qr, M, n_parts, half);
+    }
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int row = row0 + rb * 32 + acc_row(r, half);
+      float v;
+      if (row_part != nullptr)
+        v = __shfl(mine, acc_row(r, half));             // lanes 0..31 hold rows 0..31 of the block
+      else
+        v = row_const[(int64_t)g * M + min(row, M - 1)] * rc_mul;
+      rc[rb][r] = (row < M) ? v : INFINITY;              // padded rows add 2^-inf = 0
+    }
+  }
   // sum the waves' partials of one finished tile in a fixed order and store the past columns
   auto reduce_store = [&](int buf_idx, int kbase) {
     for (int j = tid; j < KT; j += NTHREADS) {
@@ -634,16 +664,19 @@ static hipError_t launch_score_mfma(const asl_params& p, const Workspace& ws, co
     ASL_LAUNCH(ws.prof, kKernRowstats, st, (score_rowstats_kernel<D, NW, RB>), dim3(Hk * n_chunks), dim3(NW * 64), 0, st, q, k,
                        p.k_stride_head, p.k_stride_tok, Hk, M, p.window, N, n_cu, n_chunks, c1,
                        ws.row_part);
-    const int rows = Hk * M;
-    ASL_LAUNCH(ws.prof, kKernCombine, st, score_combine_kernel, dim3((rows + 3) / 4), dim3(256), 0, st, ws.row_part,
-                       Hk, M, n_chunks, ws.row_const, lse_out);
+    if (lse_out) {                                 // only the row normalisers were asked for
+      const int rows = Hk * M;
+      ASL_LAUNCH(ws.prof, kKernCombine, st, score_combine_kernel, dim3((rows + 127) / 128), dim3(256), 0, st, ws.row_part,
+                         Hk, M, n_chunks, ws.row_const, lse_out);
+      return hipGetLastError();
+    }
   }
-  if (lse_out) return hipGetLastError();          // only the row normalisers were asked for
   const int n_tiles2 = (T + KT - 1) / KT;
   const int n_chunks2 = n_chunks < n_tiles2 ? n_chunks : n_tiles2;
+  // without the caller's log-sum-exp every pass-2 workgroup folds pass 1's partials of its own rows
   ASL_LAUNCH(ws.prof, kKernColsum, st, (score_colsum_kernel<D, NW, RB>), dim3(Hk * n_chunks2), dim3(NW * 64), 0, st, q, k,
                      p.k_stride_head, p.k_stride_tok, Hk, M, N, T, n_cu, c1,
-                     lse ? lse : ws.row_const, lse ? kLog2e : 1.0f, ws.u_group);
+                     lse, kLog2e, lse ? nullptr : ws.row_part, n_chunks, ws.u_group);
   return hipGetLastError();
 }
 
