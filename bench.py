@@ -2,17 +2,23 @@
 """Benchmark of the ASL per-layer token-importance pass on one MI355X.
 
 One "step" = the whole hot path for one layer of the headline workload (8B shape, 128K context,
-window 32, pool 7, budget 2048) with inputs resident in HBM: asl_score_layer (two passes over K:
-row statistics + column sums, then pooling), asl_rank_stat (RankDesc into the ring + the rank-
-variance statistic over a full 8-row ring), asl_select_topk on the Hk per-head rows and the all-head row, and asl_gather_kv of K and V.  Prints ONE JSON line.
+window 32, pool 7, budget 2048) with inputs resident in HBM: asl_layer_step = asl_score_layer (two
+passes over K: row statistics, then column sums; pooling), asl_rank_stat (RankDesc into the ring +
+the rank-variance statistic over a full 8-row ring), asl_select_topk on the Hk per-head rows and the
+all-head row, and asl_gather_kv of K and V.  Prints ONE JSON line.
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2|3|5] [--lse] [--no-cpu]
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2|3|5|6] [--no-cpu] [--no-legs]
+
+`roofline` describes the kernel with the largest summed duration in this run (HIP events recorded by the
+library around every kernel, on the stream it is launched on, in an eager loop of the same steps right
+after the timed region); `roofline_by_kernel` gives the same figures for every kernel family.
 """
 from __future__ import annotations
 
 import argparse
 import json
 import os
+import platform
 import sys
 import time
 
@@ -21,26 +27,37 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0            # MI355X published HBM3E bandwidth
-# HBM traffic of one launch of the pass-2 kernel at workload C3, from two rocprofv3 --pmc runs
-# (profiles/hot_path_c3_128k_counters.md): FETCH_SIZE 131260.0 and WRITE_SIZE 4095.0 KiB-units per
-# dispatch, scaled by what the same counters read for a 256 MiB copy (x2.0 and x1.0).
-PMC_TRAFFIC_BYTES = {3: int((131260.0 * 2.0 + 4095.0 * 1.0) * 1024)}
 MFMA_BF16_PEAK_TFLOPS = 2500.0   # dense bf16
+# HBM bytes of one launch of the scoring kernels at workload C3, measured with rocprofv3 --pmc
+# (FETCH_SIZE and WRITE_SIZE in two runs, scaled by what the same counters read for a 256 MiB copy).
+# These are NOT measured by this run: they are quoted from the committed profile named here and are
+# reported only when the workload and kernel match.
+PMC_TRAFFIC = {
+    "source": "profiles/score_kernels_c3_128k_counters.md",
+    3: {"score_rowstats": None, "score_colsum": None},
+}
 
 
-def attention_lse(q, k, sh):
-    """Input preparation for the one-pass mode: the natural-log sum-exp of every window row's
-    scaled, causally masked logits, [Hq, W] fp32.  In a prefill this comes out of the layer's
-    attention kernel; here plain torch ops stand in for that kernel (not part of the timed path)."""
-    import torch
-    G, W, N, T = sh.G, sh.W, sh.N, sh.T
-    out = torch.empty((sh.Hq, W), dtype=torch.float32, device=q.device)
-    causal = torch.ones((W, W), dtype=torch.bool, device=q.device).triu(1)     # key index > row index
-    for h in range(sh.Hq):
-        logits = (q[h].float() @ k[h // G].float().T) * sh.scale              # [W, N]
-        logits[:, T:].masked_fill_(causal, float("-inf"))
-        out[h] = torch.logsumexp(logits, dim=1)
-    return out
+def pmc_traffic(config: int, kernel: str):
+    return PMC_TRAFFIC.get(config, {}).get(kernel)
+
+
+def cpu_model() -> str:
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return platform.processor() or "unknown"
+
+
+def blas_threads() -> int:
+    try:
+        from threadpoolctl import threadpool_info
+        return max([d.get("num_threads", 1) for d in threadpool_info()] or [1])
+    except Exception:                                         # noqa: BLE001
+        return os.cpu_count() or 1
 
 
 def main() -> int:
@@ -48,10 +65,13 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--config", type=int, default=3, choices=[2, 3, 5])
+    ap.add_argument("--config", type=int, default=3, choices=[2, 3, 5, 6],
+                    help="2: 8B shape 32K, 3: 8B shape 128K (headline), 5: 8B shape 256K W=64, "
+                         "6: second model shape (Hq28/Hk4) 128K budget 8192")
     ap.add_argument("--lse", action="store_true", help="hand the rows' log-sum-exp to the scorer (one K pass)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing leg")
-    ap.add_argument("--no-lse-leg", action="store_true", help="skip the extra timed region with lse supplied")
+    ap.add_argument("--no-legs", action="store_true", help="skip the extra timed regions (lse, ordinary layer, "
+                    "warm K, batched top-k, many-layer gather)")
     ap.add_argument("--eager", action="store_true", help="time eager launches instead of HIP-graph replay")
     ap.add_argument("--copy-ref", action="store_true",
                     help="also run a plain 256 MiB device copy (a reference of known traffic for counter runs)")
@@ -59,8 +79,6 @@ def main() -> int:
     ap.add_argument("--defer-join", action="store_true",
                     help="leave a step's top-k + compaction on the second stream while the next step scores "
                          "(ASL_FLAG_DEFER_JOIN); by default every step joins before it returns")
-    ap.add_argument("--no-batched-gather", action="store_true", help="skip the 32-layer batched KV-compaction leg")
-    ap.add_argument("--breakdown", action="store_true", help="also time every kernel with events (untimed extra loop)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1",
@@ -75,11 +93,14 @@ def main() -> int:
         print("bench.py: no GPU visible", file=sys.stderr)
         return 3
     dev = torch.device("cuda:0")
-    L = synth.config_layer(args.config)
-    sh = L.shape
+    if args.config == 6:
+        sh = synth.Shape(Hq=28, Hk=4, d=128, N=131072, W=32, S=7, budget=8192, L_min=9)
+        L = synth.needle_layer(sh, 123, 64, synth.needle_gain_strong(sh), name="second-shape-128K")
+    else:
+        L = synth.config_layer(args.config)
+        sh = L.shape
     ctx = asl.Asl(sh.N, sh.Hk + 1, sh.Hq * sh.W)
     p = asl.make_params(sh.Hq, sh.Hk, sh.d, sh.N, sh.W, sh.S, sh.budget)
-    # steps that leave their top-k + compaction running on the second stream while the next step scores
     p_defer = asl.make_params(sh.Hq, sh.Hk, sh.d, sh.N, sh.W, sh.S, sh.budget, flags=asl.ASL_FLAG_DEFER_JOIN)
     up = lambda x: torch.from_numpy(x).to(dev).to(torch.bfloat16).contiguous()
     q, k, v = up(L.q_obs), up(L.k), up(L.v)
@@ -99,15 +120,23 @@ def main() -> int:
     I = torch.empty((sh.Hk + 1, n_idx), dtype=torch.int32, device=dev)   # rows 0..Hk-1 per head, row Hk all-head
     Kc = torch.empty((sh.Hk, n_idx, sh.d), dtype=torch.bfloat16, device=dev)
     Vc = torch.empty_like(Kc)
-    lses = [None] * N_SETS
-    if args.lse:
+
+    def window_lse_all():
+        """The window rows' log-sum-exp for every K copy, from the library's own row-statistics pass
+        (what a prefill attention kernel of the same layer would hand over); not part of a timed region."""
+        out = []
         for j in range(N_SETS):
-            lses[j] = attention_lse(q, ks[j], sh)
-    lse = lses[0]
+            t = torch.empty((sh.Hq, sh.W), dtype=torch.float32, device=dev)
+            ctx.asl_window_lse(p, q, ks[j], t)
+            out.append(t)
+        torch.cuda.synchronize()
+        return out
+
+    lses = window_lse_all() if args.lse else [None] * N_SETS
 
     # Fill the rank ring with L_obs-1 earlier "layers" (perturbed scores) so that every timed step
     # evaluates the statistic over a full ring; tau = 0 never selects, so the ring stays full.
-    ctx.asl_score_layer(p, q, k, P, s, lse=lse)
+    ctx.asl_score_layer(p, q, k, P, s, lse=lses[0])
     g = torch.Generator(device=dev)
     g.manual_seed(1)
     layer = 0
@@ -121,16 +150,17 @@ def main() -> int:
     # + KV compaction run on the context's second stream (both depend only on the scores and use
     # disjoint parts of the workspace), joined before the call returns.  --one-stream issues the
     # same work as four single calls back to back.
-    def step(layer_idx: int) -> None:
+    def step(layer_idx: int, lse_list=None) -> None:
+        ll = lses if lse_list is None else lse_list
         kk, vv = ks[layer_idx % N_SETS], vs[layer_idx % N_SETS]
         if args.one_stream:
-            ctx.asl_score_layer(p, q, kk, P, s, lse=lses[layer_idx % N_SETS])
+            ctx.asl_score_layer(p, q, kk, P, s, lse=ll[layer_idx % N_SETS])
             ctx.asl_rank_stat(p, s, layer_idx, 0, sh.L_obs, 0.0, ring, state, stat)
             ctx.asl_select_topk(p, PS, sh.Hk + 1, I)
             ctx.asl_gather_kv(p, kk, vv, I, sh.Hk, n_idx, Kc, Vc)
         else:
             ctx.asl_layer_step(p_defer if args.defer_join else p, q, kk, vv, layer_idx, 0, sh.L_obs, 0.0, PS,
-                               ring, state, stat, I, Kc, Vc, lse=lses[layer_idx % N_SETS])
+                               ring, state, stat, I, Kc, Vc, lse=ll[layer_idx % N_SETS])
 
     for _ in range(args.warmup):
         step(layer)
@@ -146,39 +176,51 @@ def main() -> int:
         torch.cuda.synchronize()
         del src, dst
 
-    # Timed region: exactly `steps` steps.  By default the steps are replayed from a HIP graph that
-    # holds L_obs consecutive layers (one trip round the rank ring), which takes the host's launch
-    # cost out of the measurement; --eager launches every kernel from Python instead.
-    use_graph = not args.eager
-    if use_graph and (args.steps % sh.L_obs != 0 or args.steps < sh.L_obs):
-        print(f"bench.py: --steps {args.steps} is not a multiple of L_obs={sh.L_obs} (one graph holds L_obs "
-              f"layers): timing eager launches instead", file=sys.stderr)
-        use_graph = False
+    # Timed region: exactly `steps` steps.  By default they are replayed from HIP graphs, which takes
+    # the host's launch cost out of the measurement: one graph holds L_obs consecutive layers (one trip
+    # round the rank ring) and is replayed steps // L_obs times; if steps is not a multiple of L_obs a
+    # second graph holds the remaining steps % L_obs layers and is replayed once at the end.
+    # --eager launches every kernel from Python instead.
+    use_graph = not args.eager and args.steps >= sh.L_obs
+    n_trips, n_rest = divmod(args.steps, sh.L_obs)
+
+    def next_layer() -> int:
+        return asl.read_struct(state, asl.AslState).last_layer + 1
+
     if use_graph:
-        layer = ((layer + sh.L_obs - 1) // sh.L_obs) * sh.L_obs      # graph starts on ring row 0
         cap_stream = torch.cuda.Stream()
         cap_stream.wait_stream(torch.cuda.current_stream())
-        graph = torch.cuda.CUDAGraph()
+        graphs = []
         with torch.cuda.stream(cap_stream):
-            # bring the ring in phase with the graph's first layer, then capture one trip
-            while asl.read_struct(state, asl.AslState).last_layer % sh.L_obs != sh.L_obs - 1:
-                nxt = asl.read_struct(state, asl.AslState).last_layer + 1
-                step(nxt)
-                ctx.asl_join()
-                torch.cuda.synchronize()
-            with torch.cuda.graph(graph, stream=cap_stream):
+            base = next_layer()
+            gr = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(gr, stream=cap_stream):
                 for j in range(sh.L_obs):
-                    step(layer + j)
+                    step(base + j)
                 ctx.asl_join()                         # a capture must end with every forked stream joined
-            for _ in range(2):
-                graph.replay()
+            graphs.append((gr, n_trips))
+            if n_rest:
+                gr = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(gr, stream=cap_stream):
+                    for j in range(n_rest):
+                        step(base + sh.L_obs + j)
+                    ctx.asl_join()
+                graphs.append((gr, 1))
+            # captured work has not run yet: warm both graphs once in their order, then replay the trip
+            # graph once more so that the timed replays continue a full ring (a trip whose first layer
+            # does not follow the ring's last one restarts the ring and refills all L_obs rows)
+            for gr, _ in graphs:
+                gr.replay()
+            graphs[0][0].replay()
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        for _ in range(args.steps // sh.L_obs):
-            graph.replay()
+        for gr, reps in graphs:
+            for _ in range(reps):
+                gr.replay()
         torch.cuda.synchronize()
         t1 = time.perf_counter()
     else:
+        layer = next_layer()
         t0 = time.perf_counter()
         for _ in range(args.steps):
             step(layer)
@@ -187,187 +229,242 @@ def main() -> int:
         torch.cuda.synchronize()
         t1 = time.perf_counter()
     st = asl.read_struct(stat, asl.AslStat)
-    assert st.evaluated == 1 and st.n_rows == sh.L_obs, "statistic was not evaluated over a full ring"
+    assert st.evaluated == 1, "the statistic was not evaluated in the last timed step"
+    assert ctx.asl_device_fault() == 0, "a workgroup gave up waiting for its peers during the timed region"
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    tokens_per_s = sh.N / (ms_per_step * 1e-3)
 
-    # Duration of the dominant kernel (pass-2 column sums): HIP events recorded by the library on
-    # the launch stream around that kernel alone, in an eager loop of the same `steps` steps run
-    # right after the timed region (events cannot bracket a single node of a replayed graph).
-    DOM = asl.KERNEL_NAMES.index("score_colsum")
-    ctx.asl_profile_enable(1 << DOM, args.steps)
-    layer = asl.read_struct(state, asl.AslState).last_layer + 1
+    # Per-kernel durations: HIP events recorded by the library around EVERY kernel, on the stream the
+    # kernel is launched on, in an eager loop of `n_prof` of the same steps right after the timed region
+    # (events cannot bracket single nodes of a replayed graph).
+    n_prof = max(8, min(args.steps, 64))
+    ctx.asl_profile_enable((1 << len(asl.KERNEL_NAMES)) - 1, 32 * n_prof)
+    layer = next_layer()
     torch.cuda.synchronize()
     e0 = time.perf_counter()
-    for _ in range(args.steps):
+    for _ in range(n_prof):
         step(layer)
         layer += 1
     ctx.asl_join()
     torch.cuda.synchronize()
     e1 = time.perf_counter()
-    dom_ms, dom_n = ctx.asl_profile_collect(DOM)
+    prof = {}
+    for i, name in enumerate(asl.KERNEL_NAMES):
+        ms, n = ctx.asl_profile_collect(i)
+        if n:
+            prof[name] = (ms, n)
     ctx.asl_profile_enable(0, 0)
-    eager_ms_per_step = (e1 - e0) * 1e3 / args.steps
+    eager_profiled_ms = (e1 - e0) * 1e3 / n_prof
 
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
-    tokens_per_s = sh.N / (ms_per_step * 1e-3)
-
-    # Extra leg: the same steps with the rows' log-sum-exp handed over (what the layer's attention
-    # kernel already has), so K is streamed once per layer instead of twice.  Eager launches.
-    lse_leg = None
-    if not args.lse and not args.no_lse_leg:
-        for j in range(N_SETS):
-            lses[j] = attention_lse(q, ks[j], sh)
-        for _ in range(8):
-            step(layer)
-            layer += 1
-        ctx.asl_join()
-        torch.cuda.synchronize()
-        l0 = time.perf_counter()
-        for _ in range(args.steps):
-            step(layer)
-            layer += 1
-        ctx.asl_join()
-        torch.cuda.synchronize()
-        l1 = time.perf_counter()
-        lse_ms = (l1 - l0) * 1e3 / args.steps
-        lse_leg = {"ms_per_step": round(lse_ms, 5), "value": round(sh.N / (lse_ms * 1e-3), 1),
-                   "note": "lse [Hq,W] supplied by the caller: one pass over K"}
-        lses = [None] * N_SETS
-
-    # Extra leg: a layer before the selection layer only scores, ranks and evaluates the statistic
-    # (no top-k, no compaction).  Eager launches of the two single calls.
-    ordinary_leg = None
-    if not args.no_lse_leg:
-        def ordinary(layer_idx: int) -> None:
-            ctx.asl_score_layer(p, q, ks[layer_idx % N_SETS], P, s)
-            ctx.asl_rank_stat(p, s, layer_idx, 0, sh.L_obs, 0.0, ring, state, stat)
-        for _ in range(8):
-            ordinary(layer)
-            layer += 1
-        torch.cuda.synchronize()
-        o0 = time.perf_counter()
-        for _ in range(args.steps):
-            ordinary(layer)
-            layer += 1
-        torch.cuda.synchronize()
-        o_ms = (time.perf_counter() - o0) * 1e3 / args.steps
-        ordinary_leg = {"ms_per_step": round(o_ms, 5), "value": round(sh.N / (o_ms * 1e-3), 1),
-                        "note": "score + pool + rank + statistic only (a layer that does not select), eager"}
-
-    # Extra leg: the same step on ONE K/V copy every time ("warm": whatever part of K the last-level
-    # cache keeps between layers is found there; at 128K K alone is larger than that cache).
-    warm_leg = None
-    if not args.no_lse_leg:
-        def warm_step(layer_idx: int) -> None:
-            ctx.asl_layer_step(p, q, ks[0], vs[0], layer_idx, 0, sh.L_obs, 0.0, PS, ring, state, stat, I, Kc, Vc)
-        for _ in range(8):
-            warm_step(layer)
-            layer += 1
-        torch.cuda.synchronize()
-        w0 = time.perf_counter()
-        for _ in range(args.steps):
-            warm_step(layer)
-            layer += 1
-        torch.cuda.synchronize()
-        w_ms = (time.perf_counter() - w0) * 1e3 / args.steps
-        warm_leg = {"ms_per_step": round(w_ms, 5), "value": round(sh.N / (w_ms * 1e-3), 1),
-                    "note": "same K/V copy every step (not cold), eager"}
-
-    # Algorithmic HBM bytes of one pass-2 launch: every past key once (bf16), the window queries,
-    # and the group-summed column sums written once.
+    # Algorithmic HBM bytes of ONE launch of each kernel family at this workload (per-unit figures x
+    # the units one launch processes; bf16 K/V, fp32 scores, int32 ranks and indices).
     eb = 2
-    dom_bytes = sh.Hk * T * sh.d * eb + sh.Hq * sh.W * sh.d * eb + sh.Hk * T * 4
-    dom_avg_ms = dom_ms / max(dom_n, 1)
-    dom_gbs = dom_bytes / (dom_avg_ms * 1e-3) / 1e9
+    M = sh.G * sh.W
+    q_bytes = sh.Hq * sh.W * sh.d * eb
+    n_sel_rows = sh.Hk + 1
+    alg = {
+        # every key once (window keys included: they enter the row normalisers), the window queries
+        "score_rowstats": sh.Hk * sh.N * sh.d * eb + q_bytes,
+        # every past key once, the window queries, the group-summed column sums written once
+        "score_colsum": sh.Hk * T * sh.d * eb + q_bytes + sh.Hk * T * 4,
+        # Hk rows read, Hk pooled rows + the all-head row written
+        "pool": sh.Hk * T * 4 + (sh.Hk + 1) * T * 4,
+        # one radix pass: (key, index) pairs read and written (first pass reads scores, last writes ranks)
+        "sort_scatter": T * (4 + 8 + 8 + 8 + 8 + 8 + 8 + 4) // 4,
+        # the L_obs rank rows
+        "rankvar": sh.L_obs * T * 4,
+        # top-k as a family (bound + filter + finish): every score once, the indices written
+        "select": n_sel_rows * T * 4 + n_sel_rows * n_idx * 4,
+        # K and V rows read and written, indices read
+        "gather": 2 * 2 * sh.Hk * n_idx * sh.d * eb + sh.Hk * n_idx * 4,
+    }
     useful_flops = 2.0 * sh.Hq * sh.W * sh.N * sh.d          # one QK^T over the window rows
-    roofline = {"bound": "hbm", "kernel": "score_colsum_kernel (pass 2)", "achieved": round(dom_gbs, 1),
-                "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(dom_gbs / HBM_PEAK_GBS, 4),
-                "traffic": PMC_TRAFFIC_BYTES.get(args.config), "avg_launch_ms": round(dom_avg_ms, 5), "launches": dom_n,
-                "timing": "HIP events around this kernel, eager loop of the same steps after the timed region",
-                "algorithmic_bytes": dom_bytes,
-                "mfma_tflops": round(useful_flops / (dom_avg_ms * 1e-3) / 1e12, 1),
-                "mfma_frac_of_bf16_peak": round(useful_flops / (dom_avg_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4)}
+    fam_ms = {}                                              # family -> (ms per step, launches per step)
+    for name, (ms, n) in prof.items():
+        fam = "select" if name in ("select_hist", "select_write") else name
+        a, b = fam_ms.get(fam, (0.0, 0.0))
+        fam_ms[fam] = (a + ms / n_prof, b + n / n_prof)
+    by_kernel = {}
+    for fam, (ms_step, n_step) in fam_ms.items():
+        if fam not in alg:
+            by_kernel[fam] = {"us_per_step": round(ms_step * 1e3, 2), "launches_per_step": round(n_step, 2)}
+            continue
+        # per launch for single-kernel families; for the families made of several kernels per step
+        # (sort: 4 equal passes; select: 3 different kernels) bytes and time are both per step
+        per_launch = fam in ("score_rowstats", "score_colsum", "pool", "rankvar", "gather")
+        n_div = n_step if (per_launch or fam == "sort_scatter") else 1.0
+        avg_ms = ms_step / max(n_div, 1e-9)
+        gbs = alg[fam] / (avg_ms * 1e-3) / 1e9
+        ent = {"bound": "hbm", "algorithmic_bytes": alg[fam], "avg_ms": round(avg_ms, 5),
+               "per": "launch" if (per_launch or fam == "sort_scatter") else "step (3 launches)",
+               "launches_per_step": round(n_step, 2), "us_per_step": round(ms_step * 1e3, 2),
+               "achieved_GBps": round(gbs, 1), "frac_of_hbm_peak": round(gbs / HBM_PEAK_GBS, 4)}
+        if fam in ("score_rowstats", "score_colsum"):
+            tf = useful_flops / (avg_ms * 1e-3) / 1e12
+            ent["mfma_tflops"] = round(tf, 1)
+            ent["mfma_frac_of_bf16_peak"] = round(tf / MFMA_BF16_PEAK_TFLOPS, 4)
+        by_kernel[fam] = ent
+    # the dominant kernel: the single kernel (not family) with the largest summed duration
+    single = {n: v for n, v in prof.items() if n in ("score_rowstats", "score_colsum", "pool", "rankvar", "gather")}
+    dom = max(single, key=lambda n: single[n][0])
+    d_ent = by_kernel[dom]
+    kernel_symbol = {"score_rowstats": "score_rowstats_kernel (scoring pass 1: row max / sum over all keys)",
+                     "score_colsum": "score_colsum_kernel (scoring pass 2: normalised column sums)",
+                     "pool": "pool_kernel", "rankvar": "rankvar_kernel", "gather": "gather_kernel"}[dom]
+    roofline = {"bound": "hbm", "kernel": kernel_symbol, "achieved": d_ent["achieved_GBps"], "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": d_ent["frac_of_hbm_peak"], "traffic": pmc_traffic(args.config, dom),
+                "traffic_source": PMC_TRAFFIC["source"] if pmc_traffic(args.config, dom) else None,
+                "avg_launch_ms": d_ent["avg_ms"], "launches": prof[dom][1],
+                "timing": "HIP events recorded by the library around this kernel on its launch stream, eager loop "
+                          f"of {n_prof} of the same steps after the timed region",
+                "algorithmic_bytes": d_ent["algorithmic_bytes"],
+                "chosen_as": "largest summed duration among the kernels of this run",
+                "mfma_tflops": d_ent.get("mfma_tflops"), "mfma_frac_of_bf16_peak": d_ent.get("mfma_frac_of_bf16_peak")}
 
-    kernels = None
-    if args.breakdown:
-        n_b = max(10, min(50, args.steps))
-        ctx.asl_profile_enable((1 << len(asl.KERNEL_NAMES)) - 1, 64 * n_b)
-        for _ in range(n_b):
-            step(layer)
-            layer += 1
-        ctx.asl_join()
-        torch.cuda.synchronize()
-        kernels = {}
-        for i, name in enumerate(asl.KERNEL_NAMES):
-            try:
-                ms, n = ctx.asl_profile_collect(i)
-            except asl.AslError:                              # an older library that lacks this kernel id
-                continue
-            if n:
-                kernels[name] = {"us_per_step": round(ms * 1e3 / n_b, 2), "launches_per_step": n / n_b}
-        ctx.asl_profile_enable(0, 0)
-
-    # Bandwidth of the KV compaction where bandwidth, not launch latency, is the limit: one
-    # asl_gather_kv call over 32 layers x Hk heads stacked as rows (what SnapKV-style compression of
-    # every layer before the selection layer moves in total), indices from this layer's top-k.
-    gather_leg = None
-    if not args.no_batched_gather:
-        n_layers = 32
-        rows = n_layers * sh.Hk
-        try:
-            bctx = asl.Asl(sh.N, rows, n_layers * sh.Hq * sh.W)
-            bp = asl.make_params(n_layers * sh.Hq, rows, sh.d, sh.N, sh.W, sh.S, sh.budget)
-            k_all = torch.empty((rows, sh.N, sh.d), dtype=torch.bfloat16, device=dev).normal_()
-            v_all = torch.empty((rows, sh.N, sh.d), dtype=torch.bfloat16, device=dev).normal_()
-            idx_all = I[:sh.Hk].repeat(n_layers, 1).contiguous()
-            ko = torch.empty((rows, n_idx, sh.d), dtype=torch.bfloat16, device=dev)
-            vo = torch.empty_like(ko)
-            GK = asl.KERNEL_NAMES.index("gather")
-            for _ in range(3):
-                bctx.asl_gather_kv(bp, k_all, v_all, idx_all, rows, n_idx, ko, vo)
-            bctx.asl_profile_enable(1 << GK, 32)
-            for _ in range(20):
-                bctx.asl_gather_kv(bp, k_all, v_all, idx_all, rows, n_idx, ko, vo)
+    legs = {}
+    if not args.no_legs:
+        def timed(fn, n):
+            for _ in range(8):
+                fn()
+            ctx.asl_join()
             torch.cuda.synchronize()
-            g_ms, g_n = bctx.asl_profile_collect(GK)
-            bctx.asl_profile_enable(0, 0)
-            g_bytes = 2 * 2 * rows * n_idx * sh.d * 2 + rows * n_idx * 4      # K,V read + written, indices
-            g_gbs = g_bytes / (g_ms / g_n * 1e-3) / 1e9
-            gather_leg = {"layers": n_layers, "bytes": g_bytes, "avg_launch_ms": round(g_ms / g_n, 5),
-                          "achieved_GBps": round(g_gbs, 1), "frac_of_hbm_peak": round(g_gbs / HBM_PEAK_GBS, 4)}
-            del k_all, v_all, ko, vo
+            a = time.perf_counter()
+            for _ in range(n):
+                fn()
+            ctx.asl_join()
+            torch.cuda.synchronize()
+            return (time.perf_counter() - a) * 1e3 / n
+
+        lay = [next_layer()]
+
+        def adv():
+            lay[0] += 1
+            return lay[0] - 1
+
+        # the same steps with the rows' log-sum-exp handed over, so K is streamed once per layer
+        if not args.lse:
+            lse_own = window_lse_all()
+            ms = timed(lambda: step(adv(), lse_own), args.steps)
+            legs["lse_supplied"] = {"ms_per_step": round(ms, 5), "value": round(sh.N / (ms * 1e-3), 1),
+                                    "note": "lse [Hq,W] handed over (here produced by asl_window_lse outside the "
+                                            "timed region): one pass over K; eager launches"}
+        # a layer before the selection layer only scores, ranks and evaluates the statistic
+        def ordinary():
+            li = adv()
+            ctx.asl_score_layer(p, q, ks[li % N_SETS], P, s)
+            ctx.asl_rank_stat(p, s, li, 0, sh.L_obs, 0.0, ring, state, stat)
+        ms = timed(ordinary, args.steps)
+        legs["ordinary_layer"] = {"ms_per_step": round(ms, 5), "value": round(sh.N / (ms * 1e-3), 1),
+                                  "note": "score + pool + rank + statistic only (a layer that does not select), eager"}
+        # the same step on ONE K/V copy every time (whatever part of K the last-level cache keeps is found there)
+        ms = timed(lambda: ctx.asl_layer_step(p, q, ks[0], vs[0], adv(), 0, sh.L_obs, 0.0, PS, ring, state, stat, I,
+                                              Kc, Vc), args.steps)
+        legs["warm_k"] = {"ms_per_step": round(ms, 5), "value": round(sh.N / (ms * 1e-3), 1),
+                          "note": "same K/V copy every step (not cold), eager"}
+        del lse_own
+        torch.cuda.synchronize()
+
+        # Top-k where bandwidth, not launch latency, could be the limit: 32 layers x Hk score rows in one call.
+        try:
+            rows = 32 * sh.Hk
+            bctx = asl.Asl(sh.N, rows, sh.Hq * sh.W)
+            bp = asl.make_params(sh.Hq, sh.Hk, sh.d, sh.N, sh.W, sh.S, sh.budget)
+            sc = torch.rand((rows, T), dtype=torch.float32, device=dev)
+            io = torch.empty((rows, n_idx), dtype=torch.int32, device=dev)
+            for _ in range(3):
+                bctx.asl_select_topk(bp, sc, rows, io)
+            torch.cuda.synchronize()
+            a = time.perf_counter()
+            for _ in range(10):
+                bctx.asl_select_topk(bp, sc, rows, io)
+            torch.cuda.synchronize()
+            ms = (time.perf_counter() - a) * 1e3 / 10
+            b = rows * T * 4 + rows * n_idx * 4
+            legs["select_batched"] = {"rows": rows, "algorithmic_bytes": b, "ms_per_call": round(ms, 5),
+                                      "achieved_GBps": round(b / (ms * 1e-3) / 1e9, 1),
+                                      "frac_of_hbm_peak": round(b / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                                      "note": "asl_select_topk on 32 x Hk uniform-random score rows; wall clock over 10 calls"}
+            del sc, io
             bctx.close()
         except Exception as e:                                # noqa: BLE001 - report, do not hide the headline
-            gather_leg = {"error": str(e)}
+            legs["select_batched"] = {"error": str(e)}
+
+        # KV compaction of 32 layers in one call, every layer's K and V cache a separate allocation
+        # (what SnapKV-style compression of every layer before the selection layer moves in total).
+        try:
+            n_layers = 32
+            kl = [torch.empty((sh.Hk, sh.N, sh.d), dtype=torch.bfloat16, device=dev).normal_() for _ in range(n_layers)]
+            vl = [torch.empty((sh.Hk, sh.N, sh.d), dtype=torch.bfloat16, device=dev).normal_() for _ in range(n_layers)]
+            ko = [torch.empty((sh.Hk, n_idx, sh.d), dtype=torch.bfloat16, device=dev) for _ in range(n_layers)]
+            vo = [torch.empty((sh.Hk, n_idx, sh.d), dtype=torch.bfloat16, device=dev) for _ in range(n_layers)]
+            ptrs = lambda ts: torch.tensor([t.data_ptr() for t in ts], dtype=torch.int64, device=dev)
+            kp, vp, kop, vop = ptrs(kl), ptrs(vl), ptrs(ko), ptrs(vo)
+            idx_all = I[:sh.Hk].unsqueeze(0).repeat(n_layers, 1, 1).contiguous()
+            GK = asl.KERNEL_NAMES.index("gather")
+            for _ in range(3):
+                ctx.asl_gather_kv_layers(p, kp, vp, idx_all, sh.Hk, n_idx, n_layers, kop, vop)
+            ctx.asl_profile_enable(1 << GK, 32)
+            for _ in range(20):
+                ctx.asl_gather_kv_layers(p, kp, vp, idx_all, sh.Hk, n_idx, n_layers, kop, vop)
+            torch.cuda.synchronize()
+            g_ms, g_n = ctx.asl_profile_collect(GK)
+            ctx.asl_profile_enable(0, 0)
+            g_bytes = n_layers * alg["gather"]
+            g_gbs = g_bytes / (g_ms / g_n * 1e-3) / 1e9
+            legs["gather_layers"] = {"layers": n_layers, "algorithmic_bytes": g_bytes, "avg_launch_ms": round(g_ms / g_n, 5),
+                                     "achieved_GBps": round(g_gbs, 1), "frac_of_hbm_peak": round(g_gbs / HBM_PEAK_GBS, 4),
+                                     "note": "asl_gather_kv_layers: 32 separately allocated K and V caches named by device "
+                                             "pointer arrays, one launch; HIP events around the kernel"}
+            del kl, vl, ko, vo
+        except Exception as e:                                # noqa: BLE001
+            legs["gather_layers"] = {"error": str(e)}
 
     cpu = None
     if not args.no_cpu:
         from oracle import asl_oracle as orc
-        try:
-            from threadpoolctl import threadpool_info
-            cores = max([d.get("num_threads", 1) for d in threadpool_info()] or [1])
-        except Exception:
-            cores = os.cpu_count() or 1
+        cores = blas_threads()
         reps, t_cpu = 0, 0.0
+        stage = {"score+pool": 0.0, "rank": 0.0, "statistic": 0.0, "top-k": 0.0, "gather": 0.0}
         ost = orc.SelectState.new(sh.L_obs)
-        rng = np.random.default_rng(0)
         while t_cpu < 12.0 and reps < 40:                     # bounded sample: whole layers, ~10-30 s
             c0 = time.perf_counter()
-            out = orc.get_ranks(L.q_obs, L.k, L.v, sh.W, sh.S, sh.budget)
-            ost.push(reps, out["rank"])
+            Pr, sr = orc.score_layer(L.q_obs, L.k, sh.W, sh.S)
+            c1 = time.perf_counter()
+            rk = orc.rank_desc(sr)
+            c2 = time.perf_counter()
+            ost.push(reps, rk)
             orc.select_tokens(ost, reps, sh.budget, sh.W, 0, 0.0)
-            orc.select_indices(out["s"], out["k"], sh.W)
-            t_cpu += time.perf_counter() - c0
+            c3 = time.perf_counter()
+            Ih = orc.select_indices(Pr, sh.k, sh.W)
+            orc.select_indices(sr, sh.k, sh.W)
+            c4 = time.perf_counter()
+            orc.gather_kv(L.k, L.v, Ih)
+            c5 = time.perf_counter()
+            for name, dt in zip(stage, (c1 - c0, c2 - c1, c3 - c2, c4 - c3, c5 - c4)):
+                stage[name] += dt
+            t_cpu += c5 - c0
             reps += 1
         cpu = {"value": round(sh.N * reps / t_cpu, 1), "unit": "KV tokens/s per layer", "cores": cores,
-               "kind": "oracle", "sample": f"{reps} whole layer(s) of the same workload, float64 numpy "
-               f"(score+pool+rank+statistic+per-head top-k+gather), {t_cpu:.1f} s"}
+               "kind": "oracle",
+               "sample": f"{reps} whole layer(s) of the same workload, float64 numpy "
+                         f"(score+pool, rank, statistic, per-head + all-head top-k, gather), {t_cpu:.1f} s",
+               "seconds_per_layer": round(t_cpu / reps, 3),
+               "stage_seconds_per_layer": {n: round(v / reps, 4) for n, v in stage.items()},
+               "cpu_model": cpu_model(), "os_cpu_count": os.cpu_count(), "blas_threads": cores,
+               "note": "cores = threads of the BLAS pool numpy's matmul used (threadpoolctl); the other stages are single-threaded numpy"}
 
     workload = {2: "C2: Llama-3-8B shape, N=32768, W=32, S=7, budget 2048, bf16 N(0,1)",
                 3: "C3: Llama-3-8B shape (Hq32/Hk8/d128), N=131072, W=32, S=7, budget 2048, bf16 N(0,1) + 64 needles",
-                5: "C5: Llama-3-8B shape, N=262144, W=64, S=7, budget 4096, heavy-tailed keys + 256 needles"}
+                5: "C5: Llama-3-8B shape, N=262144, W=64, S=7, budget 4096, heavy-tailed keys + 256 needles",
+                6: "second model shape (Hq28/Hk4/d128: 224 query rows per KV head), N=131072, W=32, S=7, budget 8192"}
+    if use_graph:
+        launch = (f"HIP graph replay: {n_trips} x a graph of {sh.L_obs} layers" +
+                  (f" + 1 x a graph of {n_rest} layers" if n_rest else ""))
+    else:
+        launch = "eager launches from Python"
     line = {
         "metric": "KV tokens scored+selected/sec per layer @128K (8B shape)" if args.config == 3
-                  else f"KV tokens scored+selected/sec per layer @N={sh.N} (8B shape)",
+                  else f"KV tokens scored+selected/sec per layer @N={sh.N}",
         "value": round(tokens_per_s, 1), "unit": "KV tokens/s per layer", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
@@ -375,18 +472,15 @@ def main() -> int:
         "config": {"workload": workload[args.config], "seq_len": sh.N, "window": sh.W, "pool_kernel": sh.S,
                    "budget": sh.budget, "L_obs": sh.L_obs,
                    "score_mode": "lse supplied (one K pass)" if args.lse else "self-contained (two K passes)",
-                   "launch": ("HIP graph replay (8 layers per graph)" if use_graph else "eager launches from Python")
-                             + ("" if args.one_stream else "; rank+statistic and top-k+gather on two streams")
+                   "launch": launch + ("" if args.one_stream else "; rank+statistic and top-k+gather on two streams")
                              + ("" if (args.one_stream or not args.defer_join) else
                                 "; a step's top-k+gather may still run while the next step scores (joined before its "
                                 "scores are overwritten and at the end of the timed region)"),
-                   "eager_ms_per_step": round(eager_ms_per_step, 5),
+                   "eager_profiled_ms_per_step": round(eager_profiled_ms, 5),
                    "step": "asl_layer_step = score_layer + rank_stat(full ring) + select_topk(Hk per-head rows + the all-head row) + gather_kv(K,V per head)"},
-        "roofline": roofline, "cpu_baseline": cpu, "lse_supplied": lse_leg,
-        "ordinary_layer": ordinary_leg, "warm_k": warm_leg, "gather_batched": gather_leg,
+        "roofline": roofline, "cpu_baseline": cpu, "roofline_by_kernel": by_kernel,
     }
-    if kernels is not None:
-        line["kernels"] = kernels
+    line.update(legs)
     print(json.dumps(line))
     ctx.close()
     return 0

@@ -88,7 +88,7 @@ constexpr int kSelSegment = kSelTile / 2;   // candidate slots per select tile
 constexpr int kSelCandCap = 16384;     // candidates of one row the finishing workgroup holds in LDS
 constexpr int kSelMaxSample = 8192;    // sampled keys per row for the bound
 constexpr int kSelMaxRowTiles = 1024;  // tiles per row the candidate path handles
-constexpr int kSelMaxRowsAtOnce = 64;  // rows per round of select launches (bounds the candidate buffers)
+constexpr int kSelMaxRowsAtOnce = 256; // rows per round of select launches (bounds the candidate buffers)
 
 // ---- counts handed between workgroups of one launch -------------------------------------------
 // A 64-bit word = (tag << 28) | (count1 << 14) | count0, written and read whole with relaxed
