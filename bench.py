@@ -278,6 +278,8 @@ def main() -> int:
         # K and V rows read and written, indices read
         "gather": 2 * 2 * sh.Hk * n_idx * sh.d * eb + sh.Hk * n_idx * 4,
     }
+    # asl_layer_step's four launches that each carry one sort pass and one top-k / compaction stage
+    alg["tail_fused"] = 4 * alg["sort_scatter"] + alg["select"] + alg["gather"]
     useful_flops = 2.0 * sh.Hq * sh.W * sh.N * sh.d          # one QK^T over the window rows
     fam_ms = {}                                              # family -> (ms per step, launches per step)
     for name, (ms, n) in prof.items():
@@ -296,7 +298,7 @@ def main() -> int:
         avg_ms = ms_step / max(n_div, 1e-9)
         gbs = alg[fam] / (avg_ms * 1e-3) / 1e9
         ent = {"bound": "hbm", "algorithmic_bytes": alg[fam], "avg_ms": round(avg_ms, 5),
-               "per": "launch" if (per_launch or fam == "sort_scatter") else "step (3 launches)",
+               "per": "launch" if (per_launch or fam == "sort_scatter") else f"step ({n_step:.0f} launches)",
                "launches_per_step": round(n_step, 2), "us_per_step": round(ms_step * 1e3, 2),
                "achieved_GBps": round(gbs, 1), "frac_of_hbm_peak": round(gbs / HBM_PEAK_GBS, 4)}
         if fam in ("score_rowstats", "score_colsum"):

@@ -65,8 +65,8 @@ typedef struct {
 
 /* Score with the plain fp32-FMA kernels even where the MFMA kernels apply (an on-GPU cross-check). */
 #define ASL_FLAG_GENERIC_SCORE 1
-/* asl_layer_step only: return without waiting for the top-k + compaction work on the context's
- * second stream (see asl_layer_step and asl_join). */
+/* asl_layer_step only: run top-k + compaction on the context's second stream and return without
+ * waiting for it (see asl_layer_step and asl_join). */
 #define ASL_FLAG_DEFER_JOIN 2
 
 /* Cross-layer state of Alg. 2 (init_var and the fill level of the rank cache).  24-byte device
@@ -213,23 +213,26 @@ asl_status asl_gather_kv_layers(asl_ctx* ctx, const asl_params* params, const vo
 asl_status asl_gather_rows(asl_ctx* ctx, const void* src, int64_t src_row_stride_bytes, int32_t row_bytes,
                            const int32_t* idx, int32_t n_idx, void* dst, void* stream);
 
-/* One layer of Alg. 1 + Alg. 2 in a single call: asl_score_layer, then asl_rank_stat on `stream`
- * while asl_select_topk (Hk per-head rows + the all-head row) and asl_gather_kv (per-head rows) run
- * on a second stream owned by the ctx; both are joined back into `stream` before returning, so the
- * caller sees one in-order call (also under stream capture).
+/* One layer of Alg. 1 + Alg. 2 in a single call: asl_score_layer, asl_rank_stat, asl_select_topk
+ * (Hk per-head rows + the all-head row) and asl_gather_kv (per-head rows), with the same results as
+ * the single calls.  After the scoring, ranking and top-k + compaction are independent; the call
+ * runs them side by side in four launches on `stream`, launch i carrying pass i of the ranking sort
+ * in some workgroups and stage i of the top-k / compaction in the others, followed by the statistic.
  *   scores  [Hk+1, T] f32 out: rows 0..Hk-1 = P (per KV head), row Hk = s (all heads).
  *   idx_out [Hk+1, k+W] int32 out: rows 0..Hk-1 = Alg. 1's per-head I, row Hk = Alg. 2's select_idx
  *           (to be used only when out->selected is set).
  *   k_out, v_out [Hk, k+W, d] out: K[I], V[I] per head; pass k_out = NULL to skip the compaction.
  * The ctx must have been created with max_kv_heads >= Hk + 1.  Other arguments as in the single
  * calls.  Not to be overlapped with any other call on the same ctx.
- * With ASL_FLAG_DEFER_JOIN in params->flags the call returns as soon as ranking + statistic are
- * queued on `stream`; idx_out, k_out and v_out are then complete only after asl_join.  The next
- * asl_layer_step on the ctx joins by itself before it overwrites `scores` (so in a layer loop the
- * top-k + compaction of one layer overlaps the scoring of the next); until the join, `scores`, k, v
- * and the three outputs of the deferred call must not be written or freed, and no other entry point
- * may be used on the ctx.  Call asl_join before reading the outputs and before ending a stream
- * capture (asl_destroy waits for the second stream by itself). */
+ * With ASL_FLAG_DEFER_JOIN in params->flags (and for sizes the four launches do not take) ranking +
+ * statistic run on `stream` and top-k + compaction on a second stream owned by the ctx.  With the
+ * flag the call returns as soon as ranking + statistic are queued; idx_out, k_out and v_out are then
+ * complete only after asl_join.  The next asl_layer_step on the ctx joins by itself before it
+ * overwrites `scores` (so in a layer loop the top-k + compaction of one layer overlaps the scoring
+ * of the next); until the join, `scores`, k, v and the three outputs of the deferred call must not
+ * be written or freed, and no other entry point may be used on the ctx.  Call asl_join before
+ * reading the outputs and before ending a stream capture (asl_destroy waits for the second stream
+ * by itself). */
 asl_status asl_layer_step(asl_ctx* ctx, const asl_params* params, const void* q_obs, const void* k,
                           const void* v, const float* lse, int32_t layer_idx, int32_t l_min,
                           int32_t l_obs, double tau, float* scores, int32_t* rank_ring,
@@ -253,7 +256,8 @@ asl_status asl_device_fault(asl_ctx* ctx, int32_t* fault_out);
  * calls above).  Kernel ids: 0 score row statistics (pass 1), 1 its combine, 2 score column sums
  * (pass 2), 3 pool, 4 sort histogram, 5 sort scatter, 6 rank-variance finalisation (or the
  * below-L_min skip), 7 rank-variance partial sums, 8 select histogram, 9 select write, 10 gather,
- * 11 plain-FMA score kernels.  (Each sort pass is one kernel, recorded under 5, id 4 is unused;
+ * 11 plain-FMA score kernels, 12 the four launches of asl_layer_step that carry sort passes and
+ * top-k / compaction stages together.  (Each sort pass is one kernel, recorded under 5, id 4 is unused;
  * 8 covers the top-k's bound and filter kernels, 9 its finishing kernel; the statistic is one
  * kernel, 7; 6 is the below-L_min skip.)
  * asl_profile_enable: launches whose id bit is set in kernel_mask are bracketed by HIP events on

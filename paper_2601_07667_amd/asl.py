@@ -234,7 +234,7 @@ def asl_rank_static(s, T: int, rank_out) -> None:
 
 
 KERNEL_NAMES = ["score_rowstats", "score_combine", "score_colsum", "pool", "sort_hist", "sort_scatter",
-                "rankvar_final", "rankvar", "select_hist", "select_write", "gather", "score_generic"]
+                "rankvar_final", "rankvar", "select_hist", "select_write", "gather", "score_generic", "tail_fused"]
 
 
 # -- helpers for the device-resident structs (plumbing only) ---------------------------------------

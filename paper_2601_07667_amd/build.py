@@ -10,7 +10,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libasl.so")
-SOURCES = ["api.hip", "score.hip", "pool.hip", "rank.hip", "rankvar.hip", "select.hip", "gather.hip"]
+SOURCES = ["api.hip", "score.hip", "pool.hip", "rank.hip", "rankvar.hip", "select.hip", "gather.hip", "tail.hip"]
 # packed-fp32 instructions are switched off for all device code
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

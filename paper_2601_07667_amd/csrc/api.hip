@@ -445,11 +445,10 @@ asl_status asl_select_topk(asl_ctx* ctx, const asl_params* p, const float* score
   return ASL_OK;
 }
 
-asl_status asl_gather_kv(asl_ctx* ctx, const asl_params* p, const void* k, const void* v,
-                         const int32_t* idx, int32_t idx_rows, int32_t n_idx, void* k_out,
-                         void* v_out, void* stream) {
-  asl_status st = check_params(ctx, p);
-  if (st != ASL_OK) return st;
+// Validates the operands of a one-layer KV compaction and fills the kernel's argument block.
+static asl_status make_gather_args(asl_ctx* ctx, const asl_params* p, const void* k, const void* v,
+                                   const int32_t* idx, int32_t idx_rows, int32_t n_idx, void* k_out, void* v_out,
+                                   asl::GatherArgs* out) {
   if (!k || !idx || !k_out) return fail(ctx, ASL_EINVAL, "null tensor pointer");
   if ((v == nullptr) != (v_out == nullptr)) return fail(ctx, ASL_EINVAL, "v and v_out must both be given or both be null");
   if (idx_rows != 1 && idx_rows != p->n_kv_heads)
@@ -464,8 +463,6 @@ asl_status asl_gather_kv(asl_ctx* ctx, const asl_params* p, const void* k, const
     return fail(ctx, ASL_EUNSUPPORTED, "gather needs 16-byte aligned rows, pointers and strides");
   if (p->k_stride_tok < p->head_dim || (v && p->v_stride_tok < p->head_dim))
     return fail(ctx, ASL_EINVAL, "token stride smaller than head_dim");
-  DeviceGuard guard(ctx->device);
-  if (guard.err != hipSuccess) return hip_fail(ctx, guard.err, "set device");
   asl::GatherArgs ga = {};
   ga.k = static_cast<const char*>(k);
   ga.v = static_cast<const char*>(v);
@@ -480,6 +477,20 @@ asl_status asl_gather_kv(asl_ctx* ctx, const asl_params* p, const void* k, const
   ga.n_idx = n_idx;
   ga.cpr = (int)(row_bytes / 16);
   ga.n_tensors = v ? 2 : 1;
+  *out = ga;
+  return ASL_OK;
+}
+
+asl_status asl_gather_kv(asl_ctx* ctx, const asl_params* p, const void* k, const void* v,
+                         const int32_t* idx, int32_t idx_rows, int32_t n_idx, void* k_out,
+                         void* v_out, void* stream) {
+  asl_status st = check_params(ctx, p);
+  if (st != ASL_OK) return st;
+  asl::GatherArgs ga;
+  st = make_gather_args(ctx, p, k, v, idx, idx_rows, n_idx, k_out, v_out, &ga);
+  if (st != ASL_OK) return st;
+  DeviceGuard guard(ctx->device);
+  if (guard.err != hipSuccess) return hip_fail(ctx, guard.err, "set device");
   hipError_t e = asl::launch_gather(ctx->ws.prof, ga, p->n_kv_heads, 1, static_cast<hipStream_t>(stream));
   if (e != hipSuccess) return hip_fail(ctx, e, "gather launch");
   return ASL_OK;
@@ -571,6 +582,30 @@ asl_status asl_layer_step(asl_ctx* ctx, const asl_params* p, const void* q_obs, 
   if (st != ASL_OK) return st;
   DeviceGuard guard(ctx->device);
   if (guard.err != hipSuccess) return hip_fail(ctx, guard.err, "set device");
+  if (!(p->flags & ASL_FLAG_DEFER_JOIN)) {
+    // one stream: launch i carries pass i of the ranking sort and stage i of top-k + compaction
+    if (!rank_ring || !state || !out) return fail(ctx, ASL_EINVAL, "null pointer");
+    st = rankvar_checks(ctx, l_obs, T, layer_idx, k_sel);
+    if (st != ASL_OK) return st;
+    asl::GatherArgs ga;
+    if (k_out != nullptr) {
+      st = make_gather_args(ctx, p, k, v, idx_out, Hk, k_sel + p->window, k_out, v_out, &ga);
+      if (st != ASL_OK) return st;
+    }
+    bool taken = false;
+    int32_t* row = rank_ring + (int64_t)(layer_idx % l_obs) * T;
+    hipError_t et = asl::launch_tail(ctx->ws, scores, Hk + 1, T, k_sel, p->window, row, idx_out,
+                                     k_out != nullptr ? &ga : nullptr, Hk, hs, &taken);
+    if (et != hipSuccess) return hip_fail(ctx, et, "tail launch");
+    if (taken) {
+      et = (layer_idx < l_min)
+               ? asl::launch_stat_skip(ctx->ws.prof, out, state, layer_idx, l_obs, 1, hs)
+               : asl::launch_rankvar(ctx->ws, rank_ring, l_obs, T, layer_idx, k_sel, tau, 1, state, out, hs);
+      if (et != hipSuccess) return hip_fail(ctx, et, "rankvar launch");
+      return ASL_OK;
+    }
+    // sizes these launches do not take: the two-stream sequence of single calls below
+  }
   // fork: top-k + KV compaction on the side stream, ranking + statistic on the caller's stream
   hipError_t e = hipEventRecord(ctx->ev_fork, hs);
   if (e == hipSuccess) e = hipStreamWaitEvent(ctx->side, ctx->ev_fork, 0);

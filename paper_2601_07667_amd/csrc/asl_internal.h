@@ -11,7 +11,7 @@ namespace asl {
 enum KernelId {
   kKernRowstats = 0, kKernCombine, kKernColsum, kKernPool, kKernSortHist, kKernSortScatter,
   kKernRankvarFinal, kKernRankvar, kKernSelHist, kKernSelWrite, kKernGather,
-  kKernScoreGeneric, kKernCount
+  kKernScoreGeneric, kKernTail, kKernCount
 };
 
 // Event pairs recorded around tagged launches; owned by the ctx, created by asl_profile_enable.
@@ -161,11 +161,11 @@ __device__ __forceinline__ bool flag_poll_batch(const unsigned long long* col, i
 // Workgroups of `kernel` that can wait for each other inside one launch: half of what the device
 // holds at once (other kernels may be running beside it), never more than `cap`.
 template <typename K>
-static inline int coresident_limit(K kernel, int threads, int cap = 1024) {
+static inline int coresident_limit(K kernel, int threads, int cap = 1024, size_t dynamic_lds = 0) {
   int dev = 0, cus = 0, per_cu = 0;
   if (hipGetDevice(&dev) != hipSuccess ||
       hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
-      hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, threads, 0) != hipSuccess) {
+      hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, threads, dynamic_lds) != hipSuccess) {
     (void)hipGetLastError();
     return 1;
   }
@@ -208,6 +208,11 @@ struct GatherArgs {
   int n_tensors;                 // 1 (K only) or 2 (K and V)
 };
 hipError_t launch_gather(Prof* prof, const GatherArgs& args, int Hk, int n_layers, hipStream_t st);
+bool gather_prepare(GatherArgs& a);   // sets cpr_shift; returns whether cpr is a power of two
+// Ranking sort of the last of `rows` score rows + top-k of all rows + optional KV compaction in four
+// launches on one stream (tail.hip); *taken = false when the sizes do not fit and nothing was launched.
+hipError_t launch_tail(const Workspace& ws, const float* scores, int rows, int T, int k, int W, int32_t* rank_row,
+                       int32_t* idx_out, const GatherArgs* gather, int Hk, hipStream_t st, bool* taken);
 
 bool score_mfma_supported(const asl_params& p);
 // Looks up the device address of asl_rank_static's scratch array on `device` (which must be current).

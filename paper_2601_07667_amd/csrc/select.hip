@@ -17,338 +17,56 @@
 // do not fit their buffers, step 3 runs the same selection over the whole row straight from the
 // scores instead (slower, same result).  The result therefore never depends on the sample.
 // Integer work throughout: nothing depends on scheduling.
-#include "asl_internal.h"
+#include "select_body.h"
 
 namespace asl {
 
-constexpr int kSelThreads = 256;                       // filter workgroup
-constexpr int kSelWaves = kSelThreads / 64;
-constexpr int kSelPerWave = kSelTile / kSelWaves;     // 1024
-constexpr int kSelRounds = kSelPerWave / 64;          // 16
-constexpr int kFinThreads = 1024;                      // guess / finish workgroup
-constexpr int kFinWaves = kFinThreads / 64;
-constexpr int kFinPerThread = 8;                       // consecutive elements per thread in the ordered write
-constexpr uint32_t kSegOverflow = 0xffffffffu;         // a tile's count when its segment was too small
-
-__device__ __forceinline__ uint32_t sel_key(float f) {
-  if (f == 0.0f) f = 0.0f;
-  uint32_t u = __float_as_uint(f);
-  uint32_t asc = (u & 0x80000000u) ? ~u : (u | 0x80000000u);
-  return ~asc;                                        // ascending key == descending score
+__global__ void __launch_bounds__(kFinThreads) select_guess_kernel(SelectArgs a) {
+  __shared__ GuessShared sh;
+  select_guess_body(sh, a, (int)blockIdx.x);
 }
 
-// Sample size for a row of T keys and the rank m of the sample key taken as the bound:
-// f = n_s / T of the row is sampled, the top-k members among the sample are ~Binomial(n_s, k / T)
-// with mean k f; m = k f + 5 sqrt(k f) + 4 leaves the bound too low with probability < 1e-6.
-__host__ __device__ inline int sel_sample_size(int T) {
-  int n = T / 32;
-  n = n < 1024 ? 1024 : n;
-  n = n > kSelMaxSample ? kSelMaxSample : n;
-  return n < T ? n : T;
-}
-__host__ __device__ inline int sel_sample_rank(int T, int k, int n_s) {
-  const float kf = (float)k * (float)n_s / (float)T;
-  const int m = (int)(kf + 5.0f * sqrtf(kf) + 4.0f);
-  return m;                                            // >= n_s means: no usable bound, admit everything
+// grid: x = tile, y = row
+__global__ void __launch_bounds__(kFinThreads) select_filter_kernel(SelectArgs a) {
+  __shared__ FilterShared sh;
+  select_filter_body(sh, a, (int)blockIdx.y, (int)blockIdx.x);
 }
 
-// Exclusive prefix over the workgroup's threads of two counters (kFinThreads threads), plus totals.
-__device__ __forceinline__ void block_scan2(uint32_t a, uint32_t b, uint32_t* sm /* 2*kFinWaves+2 */,
-                                            uint32_t& a_excl, uint32_t& b_excl, uint32_t& a_tot, uint32_t& b_tot) {
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-  uint32_t ai = a, bi = b;
-#pragma unroll
-  for (int o = 1; o < 64; o <<= 1) {
-    const uint32_t ua = __shfl_up(ai, o), ub = __shfl_up(bi, o);
-    if (lane >= o) {
-      ai += ua;
-      bi += ub;
-    }
-  }
-  __syncthreads();                                     // sm may still be in use
-  if (lane == 63) {
-    sm[wave] = ai;
-    sm[kFinWaves + wave] = bi;
-  }
-  __syncthreads();
-  uint32_t ab = 0, bb = 0, at = 0, bt = 0;
-  for (int w = 0; w < kFinWaves; ++w) {
-    const uint32_t x = sm[w], y = sm[kFinWaves + w];
-    ab += (w < wave) ? x : 0u;
-    bb += (w < wave) ? y : 0u;
-    at += x;
-    bt += y;
-  }
-  a_excl = ab + ai - a;
-  b_excl = bb + bi - b;
-  a_tot = at;
-  b_tot = bt;
+// dynamic LDS: kFinishLdsBytes
+__global__ void __launch_bounds__(kFinThreads) select_finish_kernel(SelectArgs a) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds_dyn[];
+  FinishShared& sh = *reinterpret_cast<FinishShared*>(lds_dyn);
+  select_finish_body(sh, reinterpret_cast<uint32_t*>(lds_dyn + sizeof(FinishShared)), a, (int)blockIdx.x);
 }
 
-// Radix select over n keys read through `key_at(i)`: returns the k-th smallest key (1 <= k <= n)
-// and how many of the keys equal to it belong to the k smallest (k_rem >= 1).  All kFinThreads
-// threads take part.  The keys' common leading bits are skipped: digits are taken from
-// key - min over the bits in which min and max differ, so the first digit already spreads the keys
-// over the bins (scores of one row share their sign and most of their exponent).
-// h: kHistWords-word LDS histogram (bank-staggered copies), sm: >= 2 * kFinWaves + 2 words.
-template <typename KeyAt>
-__device__ __forceinline__ void radix_select_block(int n, uint32_t k, KeyAt key_at, uint32_t* h, uint32_t* sm,
-                                                   uint32_t& thr_out, uint32_t& k_rem_out) {
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-  uint32_t lo = 0xffffffffu, hi = 0u;
-  for (int i = tid; i < n; i += kFinThreads) {
-    const uint32_t key = key_at(i);
-    lo = key < lo ? key : lo;
-    hi = key > hi ? key : hi;
-  }
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) {
-    const uint32_t l2 = __shfl_xor(lo, o), h2 = __shfl_xor(hi, o);
-    lo = l2 < lo ? l2 : lo;
-    hi = h2 > hi ? h2 : hi;
-  }
-  __syncthreads();                                     // sm may still be in use
-  if (lane == 0) {
-    sm[wave] = lo;
-    sm[kFinWaves + wave] = hi;
-  }
-  __syncthreads();
-  for (int w = 0; w < kFinWaves; ++w) {
-    const uint32_t l2 = sm[w], h2 = sm[kFinWaves + w];
-    lo = l2 < lo ? l2 : lo;
-    hi = h2 > hi ? h2 : hi;
-  }
-  const uint32_t span = hi - lo;
-  const int bits = span == 0 ? 0 : 32 - __clz((int)span);
-  const int n_pass = (bits + 7) / 8;                   // uniform; 0 when all keys are equal
-  uint32_t prefix = 0, k_rem = k;
-  for (int pass = 0; pass < n_pass; ++pass) {
-    const int shift = 8 * (n_pass - 1 - pass);
-    __syncthreads();                                   // h and sm of the previous pass are consumed
-    hist_clear(h, tid, kFinThreads);
-    __syncthreads();
-    for (int i = tid; i < n; i += kFinThreads) {
-      const uint32_t v = key_at(i) - lo;
-      if (pass == 0 || (v >> (shift + 8)) == prefix) hist_add(h, tid, (v >> shift) & 255u);
-    }
-    __syncthreads();
-    // exclusive scan of the 256 counts by the first four wavefronts; the digit d with
-    // excl < k_rem <= excl + count holds the k-th key
-    uint32_t cnt = 0, incl = 0;
-    if (tid < 256) {
-      cnt = hist_total(h, tid);
-      incl = cnt;
-#pragma unroll
-      for (int o = 1; o < 64; o <<= 1) {
-        const uint32_t up = __shfl_up(incl, o);
-        if (lane >= o) incl += up;
-      }
-      if (lane == 63) sm[wave] = incl;
-    }
-    if (tid == 0) {
-      sm[4] = 0;                                       // defined even if no digit qualifies
-      sm[5] = 1;                                       // (cannot happen while 1 <= k <= n)
-    }
-    __syncthreads();
-    if (tid < 256) {
-      uint32_t excl = incl - cnt;
-      for (int w = 0; w < wave; ++w) excl += sm[w];
-      if (excl < k_rem && excl + cnt >= k_rem) {       // exactly one digit satisfies this
-        sm[4] = (uint32_t)tid;
-        sm[5] = k_rem - excl;
-      }
-    }
-    __syncthreads();
-    prefix = (prefix << 8) | sm[4];
-    k_rem = sm[5];
-  }
-  thr_out = lo + prefix;
-  k_rem_out = k_rem;
-}
-
-// Step 1: bound[row] = the m-th smallest key of the row's strided sample (0xffffffff: admit all).
-__global__ void __launch_bounds__(kFinThreads)
-select_guess_kernel(const float* __restrict__ scores, int T, int row0, int k, uint32_t* __restrict__ bound) {
-  __shared__ uint32_t samp[kSelMaxSample];
-  __shared__ uint32_t h[kHistWords];
-  __shared__ uint32_t sm[2 * kFinWaves + 2];
-  const int row = row0 + blockIdx.x, tid = threadIdx.x;
-  const int n_s = sel_sample_size(T);
-  const int m = sel_sample_rank(T, k, n_s);
-  if (m >= n_s) {                                      // uniform
-    if (tid == 0) bound[row] = 0xffffffffu;
-    return;
-  }
-  const float* sr = scores + (int64_t)row * T;
-  for (int j = tid; j < n_s; j += kFinThreads)
-    samp[j] = sel_key(sr[(int)(((int64_t)j * T) / n_s)]);      // strictly increasing positions
-  uint32_t thr, k_rem;
-  radix_select_block(n_s, (uint32_t)m, [&](int i) { return samp[i]; }, h, sm, thr, k_rem);
-  if (tid == 0) bound[row] = thr;
-}
-
-// Step 2: the tile's keys <= bound, in token order, to the tile's segment of the candidate buffer.
-//   cand_key / cand_idx [rows][n_tiles][kSelSegment], seg_count [rows][n_tiles]
-__global__ void __launch_bounds__(kSelThreads)
-select_filter_kernel(const float* __restrict__ scores, int T, int n_tiles, int row0,
-                     const uint32_t* __restrict__ bound, uint32_t* __restrict__ cand_key,
-                     uint32_t* __restrict__ cand_idx, uint32_t* __restrict__ seg_count) {
-  __shared__ uint32_t wave_tot[kSelWaves];
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, tile = blockIdx.x;
-  const int row = row0 + blockIdx.y;
-  const float* sr = scores + (int64_t)row * T;
-  const int base = tile * kSelTile + wave * kSelPerWave;
-  uint32_t key[kSelRounds];
-#pragma unroll
-  for (int r = 0; r < kSelRounds; ++r) {               // all loads in flight before the first use
-    const int e = base + r * 64 + lane;
-    key[r] = (e < T) ? sel_key(sr[e]) : 0u;
-  }
-  const uint32_t b = bound[row];
-  uint32_t w_cnt = 0;
-#pragma unroll
-  for (int r = 0; r < kSelRounds; ++r) {
-    const bool keep = (base + r * 64 + lane < T) && key[r] <= b;
-    w_cnt += __popcll(__ballot(keep));
-  }
-  if (lane == 0) wave_tot[wave] = w_cnt;
-  __syncthreads();
-  uint32_t run = 0, total = 0;
-  for (int w = 0; w < kSelWaves; ++w) {
-    run += (w < wave) ? wave_tot[w] : 0u;
-    total += wave_tot[w];
-  }
-  const int64_t seg = ((int64_t)row * n_tiles + tile);
-  if (tid == 0) seg_count[seg] = (total > (uint32_t)kSelSegment) ? kSegOverflow : total;
-  if (total > (uint32_t)kSelSegment) return;           // uniform: the finish step takes the whole row instead
-  uint32_t* ck = cand_key + seg * kSelSegment;
-  uint32_t* ci = cand_idx + seg * kSelSegment;
-  const uint64_t lt_mask = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
-#pragma unroll
-  for (int r = 0; r < kSelRounds; ++r) {
-    const int e = base + r * 64 + lane;
-    const bool keep = (e < T) && key[r] <= b;
-    const uint64_t bal = __ballot(keep);
-    if (keep) {
-      const uint32_t pos = run + (uint32_t)__popcll(bal & lt_mask);
-      ck[pos] = key[r];
-      ci[pos] = (uint32_t)e;
-    }
-    run += (uint32_t)__popcll(bal);
-  }
-}
-
-// Ordered write of the kept elements of a sequence of n (key, token) pairs given in token order:
-// kept = key < thr, or key == thr and fewer than k_rem equal keys precede it.
-template <typename KeyAt, typename TokAt>
-__device__ __forceinline__ void ordered_write(int n, uint32_t thr, uint32_t k_rem, int k, KeyAt key_at, TokAt tok_at,
-                                              uint32_t* sm, int32_t* __restrict__ out) {
-  const int tid = threadIdx.x;
-  uint32_t lt_base = 0, eq_base = 0;
-  for (int c0 = 0; c0 < n; c0 += kFinThreads * kFinPerThread) {
-    const int i0 = c0 + tid * kFinPerThread;
-    uint32_t key[kFinPerThread];
-    uint32_t lt = 0, eq = 0;
-#pragma unroll
-    for (int j = 0; j < kFinPerThread; ++j) {
-      key[j] = (i0 + j < n) ? key_at(i0 + j) : 0xffffffffu;
-      lt += (i0 + j < n && key[j] < thr) ? 1u : 0u;
-      eq += (i0 + j < n && key[j] == thr) ? 1u : 0u;
-    }
-    uint32_t lt_excl, eq_excl, lt_tot, eq_tot;
-    block_scan2(lt, eq, sm, lt_excl, eq_excl, lt_tot, eq_tot);
-    uint32_t lt_run = lt_base + lt_excl, eq_run = eq_base + eq_excl;
-#pragma unroll
-    for (int j = 0; j < kFinPerThread; ++j) {
-      if (i0 + j < n) {
-        const bool is_lt = key[j] < thr, is_eq = key[j] == thr;
-        if (is_lt || (is_eq && eq_run < k_rem)) {
-          const uint32_t pos = lt_run + (eq_run < k_rem ? eq_run : k_rem);
-          if (pos < (uint32_t)k) out[pos] = (int32_t)tok_at(i0 + j);      // always true for consistent counts
-        }
-        lt_run += is_lt ? 1u : 0u;
-        eq_run += is_eq ? 1u : 0u;
-      }
-    }
-    lt_base += lt_tot;
-    eq_base += eq_tot;
-  }
-}
-
-// Step 3: one workgroup per row.  Dynamic LDS: kSelCandCap keys followed by kSelCandCap tokens.
-__global__ void __launch_bounds__(kFinThreads)
-select_finish_kernel(const float* __restrict__ scores, int T, int n_tiles, int row0, int k, int W,
-                     const uint32_t* __restrict__ cand_key, const uint32_t* __restrict__ cand_idx,
-                     const uint32_t* __restrict__ seg_count, int32_t* __restrict__ idx_out) {
-  extern __shared__ uint32_t lds_cand[];
-  __shared__ uint32_t h[kHistWords];
-  __shared__ uint32_t sm[2 * kFinWaves + 2];
-  __shared__ uint32_t seg_off[kSelMaxRowTiles + 1];
-  __shared__ int whole_row;
-  const int row = row0 + blockIdx.x, tid = threadIdx.x;
-  int32_t* out = idx_out + (int64_t)row * (k + W);
-  // offsets of the tiles' candidates in the row's candidate sequence: thread t takes tile t
-  {
-    uint32_t c = 0, over = 0;
-    if (tid < n_tiles && n_tiles <= kSelMaxRowTiles) {
-      c = seg_count[(int64_t)row * n_tiles + tid];
-      over = (c == kSegOverflow) ? 1u : 0u;
-      c = over ? 0u : c;
-    }
-    uint32_t c_excl, o_excl, c_tot, o_tot;
-    block_scan2(c, over, sm, c_excl, o_excl, c_tot, o_tot);
-    if (tid < n_tiles && n_tiles <= kSelMaxRowTiles) seg_off[tid] = c_excl;
-    if (tid == 0) {
-      if (n_tiles <= kSelMaxRowTiles) seg_off[n_tiles] = c_tot;
-      whole_row = (n_tiles > kSelMaxRowTiles || o_tot != 0 || c_tot < (uint32_t)k || c_tot > (uint32_t)kSelCandCap) ? 1 : 0;
-    }
-  }
-  __syncthreads();
-  uint32_t thr, k_rem;
-  if (!whole_row) {                                    // uniform
-    uint32_t* lk = lds_cand;
-    uint32_t* li = lds_cand + kSelCandCap;
-    const int n = (int)seg_off[n_tiles];
-    // wavefront w copies tiles w, w + kFinWaves, ...
-    for (int t = tid >> 6; t < n_tiles; t += kFinWaves) {
-      const uint32_t o = seg_off[t], c = seg_off[t + 1] - o;
-      const int64_t seg = ((int64_t)row * n_tiles + t) * kSelSegment;
-      for (uint32_t j = tid & 63; j < c; j += 64) {
-        lk[o + j] = cand_key[seg + j];
-        li[o + j] = cand_idx[seg + j];
-      }
-    }
-    __syncthreads();
-    radix_select_block(n, (uint32_t)k, [&](int i) { return lk[i]; }, h, sm, thr, k_rem);
-    ordered_write(n, thr, k_rem, k, [&](int i) { return lk[i]; }, [&](int i) { return li[i]; }, sm, out);
-  } else {
-    const float* sr = scores + (int64_t)row * T;
-    radix_select_block(T, (uint32_t)k, [&](int i) { return sel_key(sr[i]); }, h, sm, thr, k_rem);
-    ordered_write(T, thr, k_rem, k, [&](int i) { return sel_key(sr[i]); }, [&](int i) { return (uint32_t)i; }, sm, out);
-  }
-  // window tokens T .. T+W-1 (Alg. 1 step 10: Concat with I_w)
-  for (int i = tid; i < W; i += kFinThreads) out[k + i] = T + i;
+SelectArgs select_args(const Workspace& ws, const float* scores, int T, int k, int W, int32_t* idx_out) {
+  SelectArgs a = {};
+  a.scores = scores;
+  a.T = T;
+  a.n_tiles = (T + kSelTile - 1) / kSelTile;
+  a.k = k;
+  a.W = W;
+  a.bound = ws.sel_bound;
+  a.cand_key = ws.sel_cand_key;
+  a.cand_idx = ws.sel_cand_idx;
+  a.seg_count = ws.sel_seg_count;
+  a.idx_out = idx_out;
+  return a;
 }
 
 hipError_t launch_select(const Workspace& ws, const float* scores, int rows, int T, int k, int W,
                          int32_t* idx_out, hipStream_t st) {
   static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(select_finish_kernel),
-                                                     hipFuncAttributeMaxDynamicSharedMemorySize,
-                                                     2 * kSelCandCap * (int)sizeof(uint32_t));
+                                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)kFinishLdsBytes);
   if (attr != hipSuccess) return attr;
-  const int n_tiles = (T + kSelTile - 1) / kSelTile;
   // rows beyond what the candidate buffers hold at once take further rounds of the three launches
   const int rows_per_round = ws.sel_rows;
   for (int row0 = 0; row0 < rows; row0 += rows_per_round) {
     const int nr = rows - row0 < rows_per_round ? rows - row0 : rows_per_round;
-    const float* sc = scores + (int64_t)row0 * T;
-    int32_t* io = idx_out + (int64_t)row0 * (k + W);
-    ASL_LAUNCH(ws.prof, kKernSelHist, st, select_guess_kernel, dim3(nr), dim3(kFinThreads), 0, st, sc, T, 0, k, ws.sel_bound);
-    ASL_LAUNCH(ws.prof, kKernSelHist, st, select_filter_kernel, dim3(n_tiles, nr), dim3(kSelThreads), 0, st, sc, T, n_tiles,
-               0, ws.sel_bound, ws.sel_cand_key, ws.sel_cand_idx, ws.sel_seg_count);
-    ASL_LAUNCH(ws.prof, kKernSelWrite, st, select_finish_kernel, dim3(nr), dim3(kFinThreads),
-               2 * kSelCandCap * sizeof(uint32_t), st, sc, T, n_tiles, 0, k, W, ws.sel_cand_key, ws.sel_cand_idx,
-               ws.sel_seg_count, io);
+    const SelectArgs a = select_args(ws, scores + (int64_t)row0 * T, T, k, W, idx_out + (int64_t)row0 * (k + W));
+    ASL_LAUNCH(ws.prof, kKernSelHist, st, select_guess_kernel, dim3(nr), dim3(kFinThreads), 0, st, a);
+    ASL_LAUNCH(ws.prof, kKernSelHist, st, select_filter_kernel, dim3(a.n_tiles, nr), dim3(kFinThreads), 0, st, a);
+    ASL_LAUNCH(ws.prof, kKernSelWrite, st, select_finish_kernel, dim3(nr), dim3(kFinThreads), kFinishLdsBytes, st, a);
   }
   return hipGetLastError();
 }
