@@ -369,6 +369,17 @@ def test_layer_step_matches_single_calls_and_oracle(gpu_device):
         _check_layer(L, _layer_step_case(gpu_device, L))
 
 
+def test_layer_step_at_bench_size_and_beyond(gpu_device):
+    """asl_layer_step at the size the benchmark times (C3: 64 sort tiles beside the top-k stages) and at
+    2^20 tokens (the ranking sort switches to its large tiles): bit-identical to the single calls, and
+    both match the oracle."""
+    L = synth.config_layer(3)
+    _check_layer(L, _layer_step_case(gpu_device, L))
+    sh = synth.Shape(Hq=4, Hk=2, d=128, N=1 << 20, W=32, S=7, budget=8192)
+    L = synth.iid_layer(sh, 78, name="1M-step")
+    _check_layer(L, _layer_step_case(gpu_device, L))
+
+
 def test_second_model_shape_and_large_budget(gpu_device):
     """The 28-layer model's head geometry (4 KV heads, 7 query heads per group: 224 query rows per
     KV head, seven 32-row blocks) and the paper's larger KV budget of 8192."""

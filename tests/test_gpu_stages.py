@@ -211,6 +211,36 @@ def test_select_special(ctx, gpu_device):
     _select_case(ctx, gpu_device, s, T + W + 50, W)                                         # budget >= N: keep all
 
 
+@pytest.mark.parametrize("kind", ["clustered-front", "clustered-back", "few-values", "half-kept", "all-equal-large",
+                                  "sorted-desc", "sorted-asc", "one-outlier-tile"])
+def test_select_when_the_sampled_bound_does_not_help(ctx, gpu_device, kind):
+    """Inputs on which the top-k's sampled bound is useless or its candidate buffers overflow, so the
+    finishing kernel selects from the whole row: every top token inside one 4096-token tile (the tile's
+    2048-slot segment overflows), a handful of distinct values (tens of thousands of keys tie with the
+    bound), half the row kept (the candidates exceed what one workgroup holds), monotone rows."""
+    rng = np.random.default_rng(len(kind) * 31 + ord(kind[0]))
+    T, W = 70000, 32
+    budget = 2048
+    s = rng.random((3, T), dtype=np.float32)
+    if kind == "clustered-front":
+        s[:, :3000] += 10.0
+    elif kind == "clustered-back":
+        s[:, -3000:] += 10.0
+    elif kind == "few-values":
+        s = rng.integers(0, 4, (3, T)).astype(np.float32)
+    elif kind == "half-kept":
+        budget = T // 2
+    elif kind == "all-equal-large":
+        s[:] = 0.25
+    elif kind == "sorted-desc":
+        s = np.sort(s, axis=1)[:, ::-1].copy()
+    elif kind == "sorted-asc":
+        s = np.sort(s, axis=1)
+    elif kind == "one-outlier-tile":
+        s[1, 8192:12288] = 5.0 + rng.random(4096, dtype=np.float32)      # exactly one tile holds the whole top-k
+    _select_case(ctx, gpu_device, np.ascontiguousarray(s), budget, W)
+
+
 # ----------------------------------------------------------------------------- gather
 @pytest.mark.parametrize("cfg", [1, 2])
 def test_gather_bit_exact(ctx, gpu_device, cfg):
@@ -293,6 +323,14 @@ def test_argument_errors(ctx, gpu_device):
     expect(asl.ASL_EINVAL, lambda: ctx.asl_gather_kv(good, t, None, t, 3, 4, t, None))   # idx_rows not 1/Hk
     expect(asl.ASL_EINVAL, lambda: ctx.asl_rankvar(t, 1, 16, 0, 0, 4, 0.3, t, t))        # L_obs < 2
     expect(asl.ASL_EUNSUPPORTED, lambda: ctx.asl_rankvar(t, 64, 2_000_000, 0, 0, 4, 0.3, t, t))
+    # a shape without an MFMA scoring kernel (d = 96) at a size the plain kernels are not meant for
+    big = asl.Asl(1 << 20, 1, 64 * 128)
+    pb = asl.make_params(64, 1, 96, 1 << 20, 128, 7, 4096)
+    expect(asl.ASL_EUNSUPPORTED, lambda: big.asl_score_layer(pb, t, t, t, t))
+    expect(asl.ASL_EUNSUPPORTED, lambda: big.asl_window_lse(pb, t, t, t))
+    big.close()
+    # ranking more tokens than one launch can hold
+    expect(asl.ASL_ENOMEM, lambda: ctx.asl_rank(t, 1 << 22, t))
     h = C.c_void_p()
     assert ctx.lib.asl_create(C.byref(h), 0, 1, 8, 8) == asl.ASL_EINVAL
     assert ctx.lib.asl_create(C.byref(h), 99, 1024, 8, 8) == asl.ASL_EHIP
