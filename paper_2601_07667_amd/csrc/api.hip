@@ -52,6 +52,7 @@ size_t carve(char* base, int32_t max_seq_len, int32_t max_kv_heads, int32_t max_
   w.sort_epoch = (unsigned long long*)take(sizeof(unsigned long long));
   const size_t sel_tiles = (N + asl::kSelTile - 1) / asl::kSelTile;
   w.sel_rows = (int)(rows < (size_t)asl::kSelMaxRowsAtOnce ? rows : (size_t)asl::kSelMaxRowsAtOnce);
+  w.sel_sample = (uint32_t*)take((size_t)w.sel_rows * asl::kSelMaxSample * sizeof(uint32_t));
   w.sel_bound = (uint32_t*)take((size_t)w.sel_rows * sizeof(uint32_t));
   w.sel_cand_key = (uint32_t*)take((size_t)w.sel_rows * sel_tiles * asl::kSelSegment * sizeof(uint32_t));
   w.sel_cand_idx = (uint32_t*)take((size_t)w.sel_rows * sel_tiles * asl::kSelSegment * sizeof(uint32_t));
@@ -297,7 +298,8 @@ static asl_status check_score_operands(asl_ctx* ctx, const asl_params* p, const 
 // Scoring + pooling.  With wait_side set, the pooling kernel (the first one that overwrites the
 // score rows) is ordered behind the side-stream work a deferred asl_layer_step left behind.
 static asl_status score_layer_impl(asl_ctx* ctx, const asl_params* p, const void* q_obs, const void* k,
-                                   const float* lse, float* p_head, float* s_all, void* stream, bool wait_side) {
+                                   const float* lse, float* p_head, float* s_all, void* stream, bool wait_side,
+                                   bool want_sample) {
   asl_status st = check_params(ctx, p);
   if (st != ASL_OK) return st;
   if (!q_obs || !k || !p_head || !s_all) return fail(ctx, ASL_EINVAL, "null tensor pointer");
@@ -314,14 +316,15 @@ static asl_status score_layer_impl(asl_ctx* ctx, const asl_params* p, const void
     ctx->side_pending = false;
   }
   const int T = p->seq_len - p->window;
-  e = asl::launch_pool(ctx->ws.prof, ctx->ws.u_group, p->n_kv_heads, T, p->pool_kernel, p_head, s_all, hs);
+  e = asl::launch_pool(ctx->ws.prof, ctx->ws.u_group, p->n_kv_heads, T, p->pool_kernel, p_head, s_all,
+                       want_sample ? ctx->ws.sel_sample : nullptr, hs);
   if (e != hipSuccess) return hip_fail(ctx, e, "pool launch");
   return ASL_OK;
 }
 
 asl_status asl_score_layer(asl_ctx* ctx, const asl_params* p, const void* q_obs, const void* k,
                            const float* lse, float* p_head, float* s_all, void* stream) {
-  return score_layer_impl(ctx, p, q_obs, k, lse, p_head, s_all, stream, false);
+  return score_layer_impl(ctx, p, q_obs, k, lse, p_head, s_all, stream, false, false);
 }
 
 asl_status asl_window_lse(asl_ctx* ctx, const asl_params* p, const void* q_obs, const void* k,
@@ -347,7 +350,7 @@ asl_status asl_pool(asl_ctx* ctx, const float* u, int32_t rows, int32_t T, int32
   if (S > kMaxPoolKernel) return fail(ctx, ASL_EUNSUPPORTED, "pool kernel S > %d not supported", kMaxPoolKernel);
   DeviceGuard guard(ctx->device);
   if (guard.err != hipSuccess) return hip_fail(ctx, guard.err, "set device");
-  hipError_t e = asl::launch_pool(ctx->ws.prof, u, rows, T, S, p_out, s_out, static_cast<hipStream_t>(stream));
+  hipError_t e = asl::launch_pool(ctx->ws.prof, u, rows, T, S, p_out, s_out, nullptr, static_cast<hipStream_t>(stream));
   if (e != hipSuccess) return hip_fail(ctx, e, "pool launch");
   return ASL_OK;
 }
@@ -578,11 +581,13 @@ asl_status asl_layer_step(asl_ctx* ctx, const asl_params* p, const void* q_obs, 
   float* p_head = scores;
   float* s_all = scores + (int64_t)Hk * T;
   hipStream_t hs = static_cast<hipStream_t>(stream);
-  st = score_layer_impl(ctx, p, q_obs, k, lse, p_head, s_all, stream, true);
-  if (st != ASL_OK) return st;
   DeviceGuard guard(ctx->device);
   if (guard.err != hipSuccess) return hip_fail(ctx, guard.err, "set device");
-  if (!(p->flags & ASL_FLAG_DEFER_JOIN)) {
+  // when the four-launch tail will follow, the pooling kernel leaves the top-k's sample behind
+  const bool fused = !(p->flags & ASL_FLAG_DEFER_JOIN) && asl::tail_takes(ctx->ws, Hk + 1, T);
+  st = score_layer_impl(ctx, p, q_obs, k, lse, p_head, s_all, stream, true, fused);
+  if (st != ASL_OK) return st;
+  if (fused) {
     // one stream: launch i carries pass i of the ranking sort and stage i of top-k + compaction
     if (!rank_ring || !state || !out) return fail(ctx, ASL_EINVAL, "null pointer");
     st = rankvar_checks(ctx, l_obs, T, layer_idx, k_sel);
@@ -595,7 +600,7 @@ asl_status asl_layer_step(asl_ctx* ctx, const asl_params* p, const void* q_obs, 
     bool taken = false;
     int32_t* row = rank_ring + (int64_t)(layer_idx % l_obs) * T;
     hipError_t et = asl::launch_tail(ctx->ws, scores, Hk + 1, T, k_sel, p->window, row, idx_out,
-                                     k_out != nullptr ? &ga : nullptr, Hk, hs, &taken);
+                                     k_out != nullptr ? &ga : nullptr, Hk, true, hs, &taken);
     if (et != hipSuccess) return hip_fail(ctx, et, "tail launch");
     if (taken) {
       et = (layer_idx < l_min)

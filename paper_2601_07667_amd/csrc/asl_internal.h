@@ -58,6 +58,7 @@ struct Workspace {
   unsigned long long* sort_table;   // [n_tiles][128] tagged per-tile digit counts of the current pass
   unsigned long long* sort_epoch;   // [1] tag of the last sort launch
   // select
+  uint32_t* sel_sample;    // [sel_rows][kSelMaxSample] sampled keys of freshly pooled score rows
   uint32_t* sel_bound;     // [sel_rows] key bound guessed from the row's sample
   uint32_t* sel_cand_key;  // [sel_rows][n_tiles][kSelSegment] keys that passed the bound, in token order
   uint32_t* sel_cand_idx;  // same shape: their token indices
@@ -86,9 +87,19 @@ constexpr int kVarMaxBlocks = 256;     // workgroups of the rank-variance kernel
 constexpr int kSortMaxTiles = 512;     // workgroups of one sort launch (they wait for each other)
 constexpr int kSelSegment = kSelTile / 2;   // candidate slots per select tile
 constexpr int kSelCandCap = 16384;     // candidates of one row the finishing workgroup holds in LDS
-constexpr int kSelMaxSample = 8192;    // sampled keys per row for the bound
 constexpr int kSelMaxRowTiles = 1024;  // tiles per row the candidate path handles
 constexpr int kSelMaxRowsAtOnce = 256; // rows per round of select launches (bounds the candidate buffers)
+
+// ---- the strided sample the top-k takes its bound from -------------------------------------------
+// n_s = sel_sample_size(T) keys of a row at positions j * sel_sample_stride(T), j < n_s.
+constexpr int kSelMaxSample = 8192;    // sampled keys per row
+__host__ __device__ inline int sel_sample_size(int T) {
+  int n = T / 32;
+  n = n < 1024 ? 1024 : n;
+  n = n > kSelMaxSample ? kSelMaxSample : n;
+  return n < T ? n : T;
+}
+__host__ __device__ inline int sel_sample_stride(int T) { return T / sel_sample_size(T); }   // >= 1 for T >= 1
 
 // ---- counts handed between workgroups of one launch -------------------------------------------
 // A 64-bit word = (tag << 28) | (count1 << 14) | count0, written and read whole with relaxed
@@ -110,6 +121,15 @@ constexpr int kHistStride = 257;
 constexpr int kHistWords = kHistCopies * kHistStride;
 
 #ifdef __HIPCC__
+// Order-preserving 32-bit key of a score: ascending unsigned order of the keys == descending float
+// order of the scores; -0 is treated as +0.
+__device__ __forceinline__ uint32_t order_key(float f) {
+  if (f == 0.0f) f = 0.0f;
+  uint32_t u = __float_as_uint(f);
+  uint32_t asc = (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+  return ~asc;
+}
+
 __device__ __forceinline__ void hist_clear(uint32_t* h, int tid, int n_threads) {
   for (int i = tid; i < kHistWords; i += n_threads) h[i] = 0;
 }
@@ -175,8 +195,10 @@ static inline int coresident_limit(K kernel, int threads, int cap = 1024, size_t
 
 hipError_t launch_score(const asl_params& p, const Workspace& ws, const void* q_obs, const void* k,
                         const float* lse, float* lse_out, hipStream_t st);
+// sample (optional): [rows + 1][kSelMaxSample], receives the top-k's strided sample of the pooled
+// rows and, as the last row, of their sum.
 hipError_t launch_pool(Prof* prof, const float* u, int rows, int T, int S, float* p_out, float* s_out,
-                       hipStream_t st);
+                       uint32_t* sample, hipStream_t st);
 hipError_t launch_rank(const Workspace& ws, const float* s, int T, int32_t* rank_out, hipStream_t st);
 int rank_max_tiles();      // tiles (workgroups) one sort launch may have on this device
 int64_t rank_max_tokens(); // largest T one ranking call takes on this device
@@ -212,7 +234,10 @@ bool gather_prepare(GatherArgs& a);   // sets cpr_shift; returns whether cpr is 
 // Ranking sort of the last of `rows` score rows + top-k of all rows + optional KV compaction in four
 // launches on one stream (tail.hip); *taken = false when the sizes do not fit and nothing was launched.
 hipError_t launch_tail(const Workspace& ws, const float* scores, int rows, int T, int k, int W, int32_t* rank_row,
-                       int32_t* idx_out, const GatherArgs* gather, int Hk, hipStream_t st, bool* taken);
+                       int32_t* idx_out, const GatherArgs* gather, int Hk, bool have_sample, hipStream_t st,
+                       bool* taken);
+// Whether launch_tail would take these sizes (so that the pooling kernel can prepare the sample).
+bool tail_takes(const Workspace& ws, int rows, int T);
 
 bool score_mfma_supported(const asl_params& p);
 // Looks up the device address of asl_rank_static's scratch array on `device` (which must be current).

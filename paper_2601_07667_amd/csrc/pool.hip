@@ -1,5 +1,7 @@
 // asl_pool: AvgPool1D(kernel S, stride 1, zero pad floor(S/2), divisor S) along the token axis
 // (Alg. 1 step 7 of the paper), plus the sum of the pooled rows (Sec. 4.1 "scores" equation).
+// On request the kernel also leaves behind, in compact form, the strided sample of every output row
+// from which the top-k that follows takes its bound (so that nobody has to re-read the rows for it).
 #include "asl_internal.h"
 
 namespace asl {
@@ -13,7 +15,7 @@ constexpr int kPoolRows = 8;       // rows staged together
 // rows are summed in a fixed order.
 __global__ void __launch_bounds__(kPoolBlock)
 pool_kernel(const float* __restrict__ u, int rows, int T, int S, float* __restrict__ p_out,
-            float* __restrict__ s_out) {
+            float* __restrict__ s_out, uint32_t* __restrict__ sample, int n_sample, int sample_stride) {
   __shared__ float tile[kPoolRows][kPoolBlock + 2 * kPoolMaxHalf];
   const int h = S / 2;
   const int base = blockIdx.x * kPoolBlock;
@@ -21,6 +23,9 @@ pool_kernel(const float* __restrict__ u, int rows, int T, int S, float* __restri
   const int span = kPoolBlock + 2 * h;
   const float fS = (float)S;
   float total = 0.f;
+  // token t is the top-k's sample number t / stride of every row if it sits on the sample grid
+  const bool sampled = sample != nullptr && t < T && t % sample_stride == 0 && t / sample_stride < n_sample;
+  const int sample_j = sampled ? t / sample_stride : 0;
   for (int row0 = 0; row0 < rows; row0 += kPoolRows) {
     const int nr = min(kPoolRows, rows - row0);
     __syncthreads();                                   // previous group's reads are done
@@ -47,17 +52,19 @@ pool_kernel(const float* __restrict__ u, int rows, int T, int S, float* __restri
         for (int d = 0; d < S; ++d) acc += tile[r][threadIdx.x + d];   // delta = -h .. +h in order
         const float p = acc / fS;
         p_out[(int64_t)(row0 + r) * T + t] = p;
+        if (sampled) sample[(int64_t)(row0 + r) * kSelMaxSample + sample_j] = order_key(p);
         total += p;
       }
     }
   }
   if (s_out != nullptr && t < T) s_out[t] = total;
+  if (sampled) sample[(int64_t)rows * kSelMaxSample + sample_j] = order_key(total);
 }
 
 hipError_t launch_pool(Prof* prof, const float* u, int rows, int T, int S, float* p_out, float* s_out,
-                       hipStream_t st) {
+                       uint32_t* sample, hipStream_t st) {
   ASL_LAUNCH(prof, kKernPool, st, pool_kernel, dim3((T + kPoolBlock - 1) / kPoolBlock), dim3(kPoolBlock), 0, st, u,
-                     rows, T, S, p_out, s_out);
+                     rows, T, S, p_out, s_out, sample, sel_sample_size(T), sel_sample_stride(T));
   return hipGetLastError();
 }
 

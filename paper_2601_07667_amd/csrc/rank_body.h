@@ -15,14 +15,6 @@ constexpr int kSortRoundsBig = 4 * kSortRounds;
 static_assert(kSortTile % kSortThreads == 0 && kSortThreads % 128 == 0 && kSortThreads >= 256, "sort geometry");
 static_assert(kSortThreads * kSortRoundsBig < (1 << kFlagCountBits), "a tile's digit count must fit the packed field");
 
-// Ascending unsigned order of the result == descending float order; -0 is treated as +0.
-__device__ __forceinline__ uint32_t desc_key(float f) {
-  if (f == 0.0f) f = 0.0f;
-  uint32_t u = __float_as_uint(f);
-  uint32_t asc = (u & 0x80000000u) ? ~u : (u | 0x80000000u);
-  return ~asc;
-}
-
 struct SortShared {
   uint32_t h[kHistWords];
   uint32_t cnt[kSortWaves][256];
@@ -73,7 +65,7 @@ __device__ __forceinline__ void sort_pass_body(SortShared& sh, const SortArgs& a
     key[r] = 0;
     idx[r] = 0;
     if (e < a.T) {
-      key[r] = FIRST ? desc_key(a.s[e]) : a.keys_in[e];
+      key[r] = FIRST ? order_key(a.s[e]) : a.keys_in[e];
       idx[r] = FIRST ? (uint32_t)e : a.idx_in[e];
     }
   }

@@ -3,8 +3,9 @@
 // Alg. 2 steps 11-12 on the all-head scores).
 //
 // Exact selection in three small launches that read the scores once and never wait for each other:
-//  1. guess    one workgroup per row looks at an evenly strided sample of the row and takes the
-//              sample's m-th smallest key (keys are an order-preserving transform of the scores,
+//  1. guess    one workgroup per row looks at an evenly strided sample of the row (read from the
+//              scores, or left behind in compact form by the pooling kernel that produced them)
+//              and takes the sample's m-th smallest key (keys are an order-preserving transform of the scores,
 //              ascending key = descending score) as a bound that, with m a few standard deviations
 //              above the expected number of top-k members in the sample, admits at least k keys
 //              of the row and not many more;
@@ -39,9 +40,11 @@ __global__ void __launch_bounds__(kFinThreads) select_finish_kernel(SelectArgs a
   select_finish_body(sh, reinterpret_cast<uint32_t*>(lds_dyn + sizeof(FinishShared)), a, (int)blockIdx.x);
 }
 
-SelectArgs select_args(const Workspace& ws, const float* scores, int T, int k, int W, int32_t* idx_out) {
+SelectArgs select_args(const Workspace& ws, const float* scores, int T, int k, int W, int32_t* idx_out,
+                       bool have_sample) {
   SelectArgs a = {};
   a.scores = scores;
+  a.sample = have_sample ? ws.sel_sample : nullptr;
   a.T = T;
   a.n_tiles = (T + kSelTile - 1) / kSelTile;
   a.k = k;
@@ -63,7 +66,7 @@ hipError_t launch_select(const Workspace& ws, const float* scores, int rows, int
   const int rows_per_round = ws.sel_rows;
   for (int row0 = 0; row0 < rows; row0 += rows_per_round) {
     const int nr = rows - row0 < rows_per_round ? rows - row0 : rows_per_round;
-    const SelectArgs a = select_args(ws, scores + (int64_t)row0 * T, T, k, W, idx_out + (int64_t)row0 * (k + W));
+    const SelectArgs a = select_args(ws, scores + (int64_t)row0 * T, T, k, W, idx_out + (int64_t)row0 * (k + W), false);
     ASL_LAUNCH(ws.prof, kKernSelHist, st, select_guess_kernel, dim3(nr), dim3(kFinThreads), 0, st, a);
     ASL_LAUNCH(ws.prof, kKernSelHist, st, select_filter_kernel, dim3(a.n_tiles, nr), dim3(kFinThreads), 0, st, a);
     ASL_LAUNCH(ws.prof, kKernSelWrite, st, select_finish_kernel, dim3(nr), dim3(kFinThreads), kFinishLdsBytes, st, a);

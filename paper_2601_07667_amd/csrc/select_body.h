@@ -13,22 +13,9 @@ constexpr int kSelRounds = kSelPerWave / 64;          // 4
 constexpr uint32_t kSegOverflow = 0xffffffffu;         // a tile's count when its segment was too small
 static_assert(kSelTile % (64 * kFinWaves) == 0, "filter tile geometry");
 
-__device__ __forceinline__ uint32_t sel_key(float f) {
-  if (f == 0.0f) f = 0.0f;
-  uint32_t u = __float_as_uint(f);
-  uint32_t asc = (u & 0x80000000u) ? ~u : (u | 0x80000000u);
-  return ~asc;                                        // ascending key == descending score
-}
-
-// Sample size for a row of T keys and the rank m of the sample key taken as the bound:
-// f = n_s / T of the row is sampled, the top-k members among the sample are ~Binomial(n_s, k / T)
-// with mean k f; m = k f + 5 sqrt(k f) + 4 leaves the bound too low with probability < 1e-6.
-__host__ __device__ inline int sel_sample_size(int T) {
-  int n = T / 32;
-  n = n < 1024 ? 1024 : n;
-  n = n > kSelMaxSample ? kSelMaxSample : n;
-  return n < T ? n : T;
-}
+// Rank m of the sample key taken as the bound: f = n_s / T of the row is sampled, the top-k members
+// among the sample are ~Binomial(n_s, k / T) with mean k f; m = k f + 5 sqrt(k f) + 4 leaves the
+// bound too low with probability < 1e-6.
 __host__ __device__ inline int sel_sample_rank(int T, int k, int n_s) {
   const float kf = (float)k * (float)n_s / (float)T;
   const int m = (int)(kf + 5.0f * sqrtf(kf) + 4.0f);
@@ -151,6 +138,7 @@ __device__ __forceinline__ void radix_select_block(int n, uint32_t k, KeyAt key_
 
 struct SelectArgs {
   const float* scores;           // [rows][T]
+  const uint32_t* sample;        // [rows][kSelMaxSample] keys at the sample positions, or null
   int T, n_tiles, k, W;
   uint32_t* bound;               // [rows]
   uint32_t* cand_key;            // [rows][n_tiles][kSelSegment]
@@ -174,9 +162,13 @@ __device__ __forceinline__ void select_guess_body(GuessShared& sh, const SelectA
     if (tid == 0) a.bound[row] = 0xffffffffu;
     return;
   }
-  const float* sr = a.scores + (int64_t)row * T;
-  for (int j = tid; j < n_s; j += kFinThreads)
-    sh.samp[j] = sel_key(sr[(int)(((int64_t)j * T) / n_s)]);      // strictly increasing positions
+  if (a.sample != nullptr) {                           // the producer of the scores left the sample behind
+    for (int j = tid; j < n_s; j += kFinThreads) sh.samp[j] = a.sample[(int64_t)row * kSelMaxSample + j];
+  } else {
+    const float* sr = a.scores + (int64_t)row * T;
+    const int stride = sel_sample_stride(T);
+    for (int j = tid; j < n_s; j += kFinThreads) sh.samp[j] = order_key(sr[j * stride]);
+  }
   uint32_t thr, k_rem;
   radix_select_block(n_s, (uint32_t)m, [&](int i) { return sh.samp[i]; }, sh.h, sh.sm, thr, k_rem);
   if (tid == 0) a.bound[row] = thr;
@@ -195,7 +187,7 @@ __device__ __forceinline__ void select_filter_body(FilterShared& sh, const Selec
 #pragma unroll
   for (int r = 0; r < kSelRounds; ++r) {               // all loads in flight before the first use
     const int e = base + r * 64 + lane;
-    key[r] = (e < T) ? sel_key(sr[e]) : 0u;
+    key[r] = (e < T) ? order_key(sr[e]) : 0u;
   }
   const uint32_t b = a.bound[row];
   uint32_t w_cnt = 0;
@@ -319,14 +311,15 @@ __device__ __forceinline__ void select_finish_body(FinishShared& sh, uint32_t* l
     ordered_write(n, thr, k_rem, k, [&](int i) { return lk[i]; }, [&](int i) { return li[i]; }, sh.sm, out);
   } else {
     const float* sr = a.scores + (int64_t)row * T;
-    radix_select_block(T, (uint32_t)k, [&](int i) { return sel_key(sr[i]); }, sh.h, sh.sm, thr, k_rem);
-    ordered_write(T, thr, k_rem, k, [&](int i) { return sel_key(sr[i]); }, [&](int i) { return (uint32_t)i; }, sh.sm, out);
+    radix_select_block(T, (uint32_t)k, [&](int i) { return order_key(sr[i]); }, sh.h, sh.sm, thr, k_rem);
+    ordered_write(T, thr, k_rem, k, [&](int i) { return order_key(sr[i]); }, [&](int i) { return (uint32_t)i; }, sh.sm, out);
   }
   // window tokens T .. T+W-1 (Alg. 1 step 10: Concat with I_w)
   for (int i = tid; i < W; i += kFinThreads) out[k + i] = T + i;
 }
 
 // Arguments of a select over `rows` rows of scores (buffers from the workspace; rows <= ws.sel_rows).
-SelectArgs select_args(const Workspace& ws, const float* scores, int T, int k, int W, int32_t* idx_out);
+SelectArgs select_args(const Workspace& ws, const float* scores, int T, int k, int W, int32_t* idx_out,
+                       bool have_sample);
 
 }  // namespace asl

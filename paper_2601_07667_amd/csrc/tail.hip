@@ -97,9 +97,10 @@ static int tail_max_tiles() {
 
 template <int R>
 static hipError_t launch_tail_r(const Workspace& ws, const float* scores, int rows, int T, int n_tiles, int k, int W,
-                                int32_t* rank_row, int32_t* idx_out, const GatherArgs* gather, int Hk, hipStream_t st) {
+                                int32_t* rank_row, int32_t* idx_out, const GatherArgs* gather, int Hk, bool have_sample,
+                                hipStream_t st) {
   const float* s_all = scores + (int64_t)(rows - 1) * T;       // the all-head row is the last one
-  const SelectArgs se = select_args(ws, scores, T, k, W, idx_out);
+  const SelectArgs se = select_args(ws, scores, T, k, W, idx_out, have_sample);
   const dim3 block(kTailThreads);
   ASL_LAUNCH(ws.prof, kKernTail, st, (tail0_kernel<R>), dim3(n_tiles + rows), block, 0, st,
              sort_pass_args(ws, s_all, T, n_tiles, rank_row, 0), se);
@@ -130,21 +131,30 @@ static hipError_t launch_tail_r(const Workspace& ws, const float* scores, int ro
 // Ranks scores' last row into rank_row, selects the top-k of all `rows` rows into idx_out and, if
 // `gather` is given, compacts K/V with the first Hk index rows.  *taken = false (and nothing is
 // launched) when the sizes do not fit these launches; the caller then issues the single calls.
+bool tail_takes(const Workspace& ws, int rows, int T) {
+  if (rows > ws.sel_rows) return false;
+  const SortPlan small = sort_plan(T, tail_max_tiles<kSortRounds>());
+  if (small.n_tiles > 0 && !small.big) return true;
+  const int big_tile = kSortThreads * kSortRoundsBig;
+  return (T + big_tile - 1) / big_tile <= tail_max_tiles<kSortRoundsBig>();
+}
+
 hipError_t launch_tail(const Workspace& ws, const float* scores, int rows, int T, int k, int W, int32_t* rank_row,
-                       int32_t* idx_out, const GatherArgs* gather, int Hk, hipStream_t st, bool* taken) {
+                       int32_t* idx_out, const GatherArgs* gather, int Hk, bool have_sample, hipStream_t st,
+                       bool* taken) {
   *taken = false;
   if (rows > ws.sel_rows) return hipSuccess;
   if (gather != nullptr && ((int64_t)gather->n_idx * gather->cpr >= (int64_t(1) << 31))) return hipSuccess;
   const SortPlan small = sort_plan(T, tail_max_tiles<kSortRounds>());
   if (small.n_tiles > 0 && !small.big) {
     *taken = true;
-    return launch_tail_r<kSortRounds>(ws, scores, rows, T, small.n_tiles, k, W, rank_row, idx_out, gather, Hk, st);
+    return launch_tail_r<kSortRounds>(ws, scores, rows, T, small.n_tiles, k, W, rank_row, idx_out, gather, Hk, have_sample, st);
   }
   const int big_tile = kSortThreads * kSortRoundsBig;
   const int n_big = (T + big_tile - 1) / big_tile;
   if (n_big <= tail_max_tiles<kSortRoundsBig>()) {
     *taken = true;
-    return launch_tail_r<kSortRoundsBig>(ws, scores, rows, T, n_big, k, W, rank_row, idx_out, gather, Hk, st);
+    return launch_tail_r<kSortRoundsBig>(ws, scores, rows, T, n_big, k, W, rank_row, idx_out, gather, Hk, have_sample, st);
   }
   return hipSuccess;
 }
