@@ -6,7 +6,7 @@
 #include <cstring>
 #include <new>
 
-#include "asl_internal.h"
+#include "rankvar_body.h"
 
 struct asl_ctx {
   int device;
@@ -54,6 +54,7 @@ size_t carve(char* base, int32_t max_seq_len, int32_t max_kv_heads, int32_t max_
   w.sel_rows = (int)(rows < (size_t)asl::kSelMaxRowsAtOnce ? rows : (size_t)asl::kSelMaxRowsAtOnce);
   w.sel_sample = (uint32_t*)take((size_t)w.sel_rows * asl::kSelMaxSample * sizeof(uint32_t));
   w.sel_bound = (uint32_t*)take((size_t)w.sel_rows * sizeof(uint32_t));
+  w.sel_thr = (uint32_t*)take((size_t)w.sel_rows * 2 * sizeof(uint32_t));
   w.sel_cand_key = (uint32_t*)take((size_t)w.sel_rows * sel_tiles * asl::kSelSegment * sizeof(uint32_t));
   w.sel_cand_idx = (uint32_t*)take((size_t)w.sel_rows * sel_tiles * asl::kSelSegment * sizeof(uint32_t));
   w.sel_seg_count = (uint32_t*)take((size_t)w.sel_rows * sel_tiles * sizeof(uint32_t));
@@ -599,14 +600,18 @@ asl_status asl_layer_step(asl_ctx* ctx, const asl_params* p, const void* q_obs, 
     }
     bool taken = false;
     int32_t* row = rank_ring + (int64_t)(layer_idx % l_obs) * T;
+    // below L_min nothing is evaluated: the statistic's place in the last launch stays empty and the
+    // state is advanced by the one-thread kernel instead
+    const asl::RankvarArgs ra = asl::rankvar_args(ctx->ws, rank_ring, l_obs, T, layer_idx, k_sel, tau, 1, state, out);
     hipError_t et = asl::launch_tail(ctx->ws, scores, Hk + 1, T, k_sel, p->window, row, idx_out,
-                                     k_out != nullptr ? &ga : nullptr, Hk, true, hs, &taken);
+                                     k_out != nullptr ? &ga : nullptr, Hk, true, layer_idx < l_min ? nullptr : &ra, hs,
+                                     &taken);
     if (et != hipSuccess) return hip_fail(ctx, et, "tail launch");
     if (taken) {
-      et = (layer_idx < l_min)
-               ? asl::launch_stat_skip(ctx->ws.prof, out, state, layer_idx, l_obs, 1, hs)
-               : asl::launch_rankvar(ctx->ws, rank_ring, l_obs, T, layer_idx, k_sel, tau, 1, state, out, hs);
-      if (et != hipSuccess) return hip_fail(ctx, et, "rankvar launch");
+      if (layer_idx < l_min) {
+        et = asl::launch_stat_skip(ctx->ws.prof, out, state, layer_idx, l_obs, 1, hs);
+        if (et != hipSuccess) return hip_fail(ctx, et, "rankvar launch");
+      }
       return ASL_OK;
     }
     // sizes these launches do not take: the two-stream sequence of single calls below

@@ -60,6 +60,7 @@ struct Workspace {
   // select
   uint32_t* sel_sample;    // [sel_rows][kSelMaxSample] sampled keys of freshly pooled score rows
   uint32_t* sel_bound;     // [sel_rows] key bound guessed from the row's sample
+  uint32_t* sel_thr;       // [sel_rows][2] threshold key and kept ties of each row
   uint32_t* sel_cand_key;  // [sel_rows][n_tiles][kSelSegment] keys that passed the bound, in token order
   uint32_t* sel_cand_idx;  // same shape: their token indices
   uint32_t* sel_seg_count; // [sel_rows][n_tiles] entries used in each segment
@@ -231,11 +232,12 @@ struct GatherArgs {
 };
 hipError_t launch_gather(Prof* prof, const GatherArgs& args, int Hk, int n_layers, hipStream_t st);
 bool gather_prepare(GatherArgs& a);   // sets cpr_shift; returns whether cpr is a power of two
-// Ranking sort of the last of `rows` score rows + top-k of all rows + optional KV compaction in four
-// launches on one stream (tail.hip); *taken = false when the sizes do not fit and nothing was launched.
+// Ranking sort of the last of `rows` score rows + top-k of all rows + optional statistic and KV
+// compaction in five launches on one stream (tail.hip); *taken = false when the sizes do not fit and nothing was launched.
+struct RankvarArgs;
 hipError_t launch_tail(const Workspace& ws, const float* scores, int rows, int T, int k, int W, int32_t* rank_row,
-                       int32_t* idx_out, const GatherArgs* gather, int Hk, bool have_sample, hipStream_t st,
-                       bool* taken);
+                       int32_t* idx_out, const GatherArgs* gather, int Hk, bool have_sample, const RankvarArgs* stat,
+                       hipStream_t st, bool* taken);
 // Whether launch_tail would take these sizes (so that the pooling kernel can prepare the sample).
 bool tail_takes(const Workspace& ws, int rows, int T);
 

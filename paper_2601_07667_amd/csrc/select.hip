@@ -50,6 +50,7 @@ SelectArgs select_args(const Workspace& ws, const float* scores, int T, int k, i
   a.k = k;
   a.W = W;
   a.bound = ws.sel_bound;
+  a.thr = ws.sel_thr;
   a.cand_key = ws.sel_cand_key;
   a.cand_idx = ws.sel_cand_idx;
   a.seg_count = ws.sel_seg_count;

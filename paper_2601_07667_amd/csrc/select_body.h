@@ -141,6 +141,7 @@ struct SelectArgs {
   const uint32_t* sample;        // [rows][kSelMaxSample] keys at the sample positions, or null
   int T, n_tiles, k, W;
   uint32_t* bound;               // [rows]
+  uint32_t* thr;                 // [rows][2] (threshold key, kept ties) when step 3 spans two launches
   uint32_t* cand_key;            // [rows][n_tiles][kSelSegment]
   uint32_t* cand_idx;
   uint32_t* seg_count;           // [rows][n_tiles]
@@ -271,13 +272,14 @@ struct FinishShared {
 };
 constexpr size_t kFinishLdsBytes = sizeof(FinishShared) + 2 * (size_t)kSelCandCap * sizeof(uint32_t);
 
-// Step 3: one workgroup per row.
-__device__ __forceinline__ void select_finish_body(FinishShared& sh, uint32_t* lds_cand, const SelectArgs& a, int row) {
-  const int tid = threadIdx.x, T = a.T, n_tiles = a.n_tiles, k = a.k, W = a.W;
-  int32_t* out = a.idx_out + (int64_t)row * (k + W);
-  // offsets of the tiles' candidates in the row's candidate sequence: thread t takes tile t
+// Step 3 has two halves, usable from one kernel or from two consecutive launches.
+// Common start: offsets of the tiles' candidates in the row's candidate sequence and, unless the
+// whole row has to be taken instead (sh.whole_row), the candidates copied into LDS.  Returns the
+// number of candidates.
+__device__ __forceinline__ int finish_load(FinishShared& sh, uint32_t* lds_cand, const SelectArgs& a, int row) {
+  const int tid = threadIdx.x, n_tiles = a.n_tiles, k = a.k;
   {
-    uint32_t c = 0, over = 0;
+    uint32_t c = 0, over = 0;                          // thread t takes tile t
     if (tid < n_tiles && n_tiles <= kSelMaxRowTiles) {
       c = a.seg_count[(int64_t)row * n_tiles + tid];
       over = (c == kSegOverflow) ? 1u : 0u;
@@ -292,30 +294,73 @@ __device__ __forceinline__ void select_finish_body(FinishShared& sh, uint32_t* l
     }
   }
   __syncthreads();
-  uint32_t thr, k_rem;
-  if (!sh.whole_row) {                                 // uniform
-    uint32_t* lk = lds_cand;
-    uint32_t* li = lds_cand + kSelCandCap;
-    const int n = (int)sh.seg_off[n_tiles];
-    // wavefront w copies tiles w, w + kFinWaves, ...
-    for (int t = tid >> 6; t < n_tiles; t += kFinWaves) {
-      const uint32_t o = sh.seg_off[t], c = sh.seg_off[t + 1] - o;
-      const int64_t seg = ((int64_t)row * n_tiles + t) * kSelSegment;
-      for (uint32_t j = tid & 63; j < c; j += 64) {
-        lk[o + j] = a.cand_key[seg + j];
-        li[o + j] = a.cand_idx[seg + j];
-      }
+  if (sh.whole_row) return 0;                          // uniform
+  uint32_t* lk = lds_cand;
+  uint32_t* li = lds_cand + kSelCandCap;
+  // wavefront w copies tiles w, w + kFinWaves, ...
+  for (int t = tid >> 6; t < n_tiles; t += kFinWaves) {
+    const uint32_t o = sh.seg_off[t], c = sh.seg_off[t + 1] - o;
+    const int64_t seg = ((int64_t)row * n_tiles + t) * kSelSegment;
+    for (uint32_t j = tid & 63; j < c; j += 64) {
+      lk[o + j] = a.cand_key[seg + j];
+      li[o + j] = a.cand_idx[seg + j];
     }
-    __syncthreads();
-    radix_select_block(n, (uint32_t)k, [&](int i) { return lk[i]; }, sh.h, sh.sm, thr, k_rem);
+  }
+  __syncthreads();
+  return (int)sh.seg_off[n_tiles];
+}
+
+// First half: the k-th smallest key of the row and how many keys equal to it are kept.
+// n: finish_load's result.  With `publish` the pair is also stored for a later launch.
+__device__ __forceinline__ void finish_threshold(FinishShared& sh, const uint32_t* lds_cand, const SelectArgs& a, int row,
+                                                 int n, bool publish, uint32_t& thr, uint32_t& k_rem) {
+  if (!sh.whole_row) {                                 // uniform
+    radix_select_block(n, (uint32_t)a.k, [&](int i) { return lds_cand[i]; }, sh.h, sh.sm, thr, k_rem);
+  } else {
+    const float* sr = a.scores + (int64_t)row * a.T;
+    radix_select_block(a.T, (uint32_t)a.k, [&](int i) { return order_key(sr[i]); }, sh.h, sh.sm, thr, k_rem);
+  }
+  if (publish && threadIdx.x == 0) {
+    a.thr[2 * row] = thr;
+    a.thr[2 * row + 1] = k_rem;
+  }
+}
+
+// Second half: the kept tokens in ascending order, then the window tokens.
+__device__ __forceinline__ void finish_write(FinishShared& sh, const uint32_t* lds_cand, const SelectArgs& a, int row,
+                                             int n, uint32_t thr, uint32_t k_rem) {
+  const int tid = threadIdx.x, T = a.T, k = a.k, W = a.W;
+  int32_t* out = a.idx_out + (int64_t)row * (k + W);
+  if (!sh.whole_row) {                                 // uniform
+    const uint32_t* lk = lds_cand;
+    const uint32_t* li = lds_cand + kSelCandCap;
     ordered_write(n, thr, k_rem, k, [&](int i) { return lk[i]; }, [&](int i) { return li[i]; }, sh.sm, out);
   } else {
     const float* sr = a.scores + (int64_t)row * T;
-    radix_select_block(T, (uint32_t)k, [&](int i) { return order_key(sr[i]); }, sh.h, sh.sm, thr, k_rem);
     ordered_write(T, thr, k_rem, k, [&](int i) { return order_key(sr[i]); }, [&](int i) { return (uint32_t)i; }, sh.sm, out);
   }
   // window tokens T .. T+W-1 (Alg. 1 step 10: Concat with I_w)
   for (int i = tid; i < W; i += kFinThreads) out[k + i] = T + i;
+}
+
+// Step 3 in one kernel: one workgroup per row.
+__device__ __forceinline__ void select_finish_body(FinishShared& sh, uint32_t* lds_cand, const SelectArgs& a, int row) {
+  const int n = finish_load(sh, lds_cand, a, row);
+  uint32_t thr, k_rem;
+  finish_threshold(sh, lds_cand, a, row, n, false, thr, k_rem);
+  finish_write(sh, lds_cand, a, row, n, thr, k_rem);
+}
+
+// Step 3 over two launches: the first stores (threshold key, kept ties) of every row in a.thr ...
+__device__ __forceinline__ void select_threshold_body(FinishShared& sh, uint32_t* lds_cand, const SelectArgs& a, int row) {
+  const int n = finish_load(sh, lds_cand, a, row);
+  uint32_t thr, k_rem;
+  finish_threshold(sh, lds_cand, a, row, n, true, thr, k_rem);
+}
+// ... the second loads the candidates again and writes the indices.
+__device__ __forceinline__ void select_write_body(FinishShared& sh, uint32_t* lds_cand, const SelectArgs& a, int row) {
+  const int n = finish_load(sh, lds_cand, a, row);
+  finish_write(sh, lds_cand, a, row, n, a.thr[2 * row], a.thr[2 * row + 1]);
 }
 
 // Arguments of a select over `rows` rows of scores (buffers from the workspace; rows <= ws.sel_rows).
