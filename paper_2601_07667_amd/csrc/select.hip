@@ -28,9 +28,9 @@ __global__ void __launch_bounds__(kFinThreads) select_guess_kernel(SelectArgs a)
 }
 
 // grid: x = tile, y = row
-__global__ void __launch_bounds__(kFinThreads) select_filter_kernel(SelectArgs a) {
+__global__ void __launch_bounds__(kFilterThreads) select_filter_kernel(SelectArgs a) {
   __shared__ FilterShared sh;
-  select_filter_body(sh, a, (int)blockIdx.y, (int)blockIdx.x);
+  select_filter_body<kFilterThreads>(sh, a, (int)blockIdx.y, (int)blockIdx.x);
 }
 
 // dynamic LDS: kFinishLdsBytes
@@ -69,7 +69,7 @@ hipError_t launch_select(const Workspace& ws, const float* scores, int rows, int
     const int nr = rows - row0 < rows_per_round ? rows - row0 : rows_per_round;
     const SelectArgs a = select_args(ws, scores + (int64_t)row0 * T, T, k, W, idx_out + (int64_t)row0 * (k + W), false);
     ASL_LAUNCH(ws.prof, kKernSelHist, st, select_guess_kernel, dim3(nr), dim3(kFinThreads), 0, st, a);
-    ASL_LAUNCH(ws.prof, kKernSelHist, st, select_filter_kernel, dim3(a.n_tiles, nr), dim3(kFinThreads), 0, st, a);
+    ASL_LAUNCH(ws.prof, kKernSelHist, st, select_filter_kernel, dim3(a.n_tiles, nr), dim3(kFilterThreads), 0, st, a);
     ASL_LAUNCH(ws.prof, kKernSelWrite, st, select_finish_kernel, dim3(nr), dim3(kFinThreads), kFinishLdsBytes, st, a);
   }
   return hipGetLastError();

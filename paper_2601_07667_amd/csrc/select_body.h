@@ -8,19 +8,23 @@ namespace asl {
 constexpr int kFinThreads = 1024;                      // workgroup of all three kernels
 constexpr int kFinWaves = kFinThreads / 64;
 constexpr int kFinPerThread = 8;                       // consecutive elements per thread in the ordered write
-constexpr int kSelPerWave = kSelTile / kFinWaves;     // 256 tokens of a filter tile per wavefront
-constexpr int kSelRounds = kSelPerWave / 64;          // 4
+constexpr int kFilterThreads = 256;                    // filter workgroup when it runs as its own launch
 constexpr uint32_t kSegOverflow = 0xffffffffu;         // a tile's count when its segment was too small
-static_assert(kSelTile % (64 * kFinWaves) == 0, "filter tile geometry");
+static_assert(kSelTile % kFinThreads == 0 && kSelTile % kFilterThreads == 0, "filter tile geometry");
 
 // Rank m of the sample key taken as the bound: f = n_s / T of the row is sampled, the top-k members
-// among the sample are ~Binomial(n_s, k / T) with mean k f; m = k f + 5 sqrt(k f) + 4 leaves the
-// bound too low with probability < 1e-6.
-__host__ __device__ inline int sel_sample_rank(int T, int k, int n_s) {
+// among the sample are ~Binomial(n_s, k / T) with mean k f; m = k f + 5 sqrt(c k f) + 4 leaves the
+// bound too low with probability < 1e-6.  c = 1 for single sampled keys; c = `run` when the sample
+// consists of runs of `run` neighbouring keys, which may be as correlated as identical (pooled
+// scores are): the count's variance is then at most `run` times the binomial one.
+__host__ __device__ inline int sel_sample_rank(int T, int k, int n_s, int run) {
   const float kf = (float)k * (float)n_s / (float)T;
-  const int m = (int)(kf + 5.0f * sqrtf(kf) + 4.0f);
+  const int m = (int)(kf + 5.0f * sqrtf((float)run * kf) + 4.0f);
   return m;                                            // >= n_s means: no usable bound, admit everything
 }
+// Without a prepared sample the bound kernel reads runs of kSelSampleRun neighbouring keys, one run
+// per kSelSampleRun sample strides: the same number of keys from a quarter of the cache lines.
+constexpr int kSelSampleRun = 4;
 
 // Exclusive prefix over the workgroup's threads of two counters (kFinThreads threads), plus totals.
 __device__ __forceinline__ void block_scan2(uint32_t a, uint32_t b, uint32_t* sm /* 2*kFinWaves+2 */,
@@ -157,8 +161,10 @@ struct GuessShared {
 // Step 1: bound[row] = the m-th smallest key of the row's strided sample (0xffffffff: admit all).
 __device__ __forceinline__ void select_guess_body(GuessShared& sh, const SelectArgs& a, int row) {
   const int tid = threadIdx.x, T = a.T;
-  const int n_s = sel_sample_size(T);
-  const int m = sel_sample_rank(T, a.k, n_s);
+  const int stride = sel_sample_stride(T);
+  const bool runs = a.sample == nullptr && stride >= 2;           // stride 1: the sample is the row itself
+  const int n_s = runs ? (sel_sample_size(T) / kSelSampleRun) * kSelSampleRun : sel_sample_size(T);
+  const int m = sel_sample_rank(T, a.k, n_s, runs ? kSelSampleRun : 1);
   if (m >= n_s) {                                      // uniform
     if (tid == 0) a.bound[row] = 0xffffffffu;
     return;
@@ -167,8 +173,12 @@ __device__ __forceinline__ void select_guess_body(GuessShared& sh, const SelectA
     for (int j = tid; j < n_s; j += kFinThreads) sh.samp[j] = a.sample[(int64_t)row * kSelMaxSample + j];
   } else {
     const float* sr = a.scores + (int64_t)row * T;
-    const int stride = sel_sample_stride(T);
-    for (int j = tid; j < n_s; j += kFinThreads) sh.samp[j] = order_key(sr[j * stride]);
+    if (runs) {                                        // key j = member j % run of run j / run
+      for (int j = tid; j < n_s; j += kFinThreads)
+        sh.samp[j] = order_key(sr[(j / kSelSampleRun) * (kSelSampleRun * stride) + (j % kSelSampleRun)]);
+    } else {
+      for (int j = tid; j < n_s; j += kFinThreads) sh.samp[j] = order_key(sr[j * stride]);
+    }
   }
   uint32_t thr, k_rem;
   radix_select_block(n_s, (uint32_t)m, [&](int i) { return sh.samp[i]; }, sh.h, sh.sm, thr, k_rem);
@@ -180,7 +190,10 @@ struct FilterShared {
 };
 
 // Step 2: the tile's keys <= bound, in token order, to the tile's segment of the candidate buffer.
+// NT threads per workgroup: each wavefront takes kSelTile / (NT / 64) consecutive tokens.
+template <int NT>
 __device__ __forceinline__ void select_filter_body(FilterShared& sh, const SelectArgs& a, int row, int tile) {
+  constexpr int kWaves = NT / 64, kSelPerWave = kSelTile / kWaves, kSelRounds = kSelPerWave / 64;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, T = a.T;
   const float* sr = a.scores + (int64_t)row * T;
   const int base = tile * kSelTile + wave * kSelPerWave;
@@ -200,7 +213,7 @@ __device__ __forceinline__ void select_filter_body(FilterShared& sh, const Selec
   if (lane == 0) sh.wave_tot[wave] = w_cnt;
   __syncthreads();
   uint32_t run = 0, total = 0;
-  for (int w = 0; w < kFinWaves; ++w) {
+  for (int w = 0; w < kWaves; ++w) {
     run += (w < wave) ? sh.wave_tot[w] : 0u;
     total += sh.wave_tot[w];
   }

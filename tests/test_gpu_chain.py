@@ -378,6 +378,12 @@ def test_layer_step_at_bench_size_and_beyond(gpu_device):
     sh = synth.Shape(Hq=4, Hk=2, d=128, N=1 << 20, W=32, S=7, budget=8192)
     L = synth.iid_layer(sh, 78, name="1M-step")
     _check_layer(L, _layer_step_case(gpu_device, L))
+    # the other shapes the benchmark times: 256K / W = 64 (128 sort tiles) and the second model shape with
+    # budget 8192 (5 score rows); here against the single calls only (their oracle parity is tested above)
+    _layer_step_case(gpu_device, synth.config_layer(5), layer_idx=12)
+    sh = synth.Shape(Hq=28, Hk=4, d=128, N=131072, W=32, S=7, budget=8192, L_min=9)
+    _layer_step_case(gpu_device, synth.needle_layer(sh, 123, 64, synth.needle_gain_strong(sh), name="second-shape-128K"),
+                     layer_idx=3)
 
 
 def test_second_model_shape_and_large_budget(gpu_device):

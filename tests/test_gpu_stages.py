@@ -63,6 +63,22 @@ def test_rank_random_with_ties(ctx, gpu_device, T):
     _rank_case(ctx, gpu_device, s)
 
 
+@pytest.mark.parametrize("T", [524288, 524289, 700001])
+def test_rank_beyond_the_small_tile_limit(gpu_device, T):
+    """Above 256 tiles of 2048 the sort switches to tiles of 8192 elements: the last size that still uses
+    the small tiles, the first that does not, and a ragged larger one."""
+    torch = _torch()
+    c = asl.Asl(T, 1, 32)
+    rng = np.random.default_rng(T)
+    s = np.round(rng.standard_normal(T), 2).astype(np.float32)        # heavy ties
+    sd = torch.from_numpy(s).to(gpu_device)
+    out = torch.full((T,), -1, dtype=torch.int32, device=gpu_device)
+    c.asl_rank(sd, T, out)
+    np.testing.assert_array_equal(out.cpu().numpy().astype(np.int64), orc.rank_desc(s.astype(np.float64)))
+    assert c.asl_device_fault() == 0
+    c.close()
+
+
 def test_rank_special(ctx, gpu_device):
     T = 5000
     _rank_case(ctx, gpu_device, np.ones(T, dtype=np.float32))                               # all equal
