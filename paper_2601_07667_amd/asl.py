@@ -60,6 +60,12 @@ def load() -> C.CDLL:
         return _lib
     if not os.path.exists(LIB_PATH):
         raise ImportError(f"{LIB_PATH} not found: build it with `python -m paper_2601_07667_amd.build`")
+    # The tensors handed to the library are PyTorch allocations, so the process must run ONE HIP runtime:
+    # the one PyTorch ships.  Loading it first makes libasl.so bind to it instead of pulling in a second copy.
+    try:
+        import torch  # noqa: F401
+    except ImportError:
+        pass
     lib = C.CDLL(LIB_PATH)
     vp, i32, i64 = C.c_void_p, C.c_int32, C.c_int64
     lib.asl_create.argtypes = [C.POINTER(vp), C.c_int, i32, i32, i32]
