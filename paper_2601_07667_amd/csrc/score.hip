@@ -50,8 +50,8 @@ __device__ __forceinline__ int acc_row(int r, int half) { return 8 * (r >> 2) + 
 // fragment reads are avoided by an XOR swizzle applied on the global side: LDS slot (row r,
 // piece c') holds the row's 16-byte piece  c = c' ^ (r mod CPR).
 // Rows past N are clamped to the last key (they are masked or discarded later).
-// Per-thread constants of the tile loader: for each of its NLOAD pieces the tile row and the byte
-// offset of the (swizzled) source piece from the tile's first key.
+// Per-thread constants of the tile loader: for each of its NLOAD pieces the byte offset of the
+// (swizzled) source piece from the tile's first key.
 // The first NT threads of the workgroup do the loading, NT = the largest power of two that is at most
 // the workgroup size and the number of pieces (see loader_threads): every loading wavefront then
 // issues the same number of loads per tile, which the counted waits below rely on; the other
@@ -63,17 +63,15 @@ struct TilePieces {
   static_assert(SLOTS % NT == 0, "loader threads must divide the pieces of a tile");
   static constexpr int NLOAD = SLOTS / NT;
   uint32_t src_off[NLOAD];
-  int row[NLOAD];
-  int col8[NLOAD];
+  // tile row and first element of the (swizzled) source piece of this thread's i-th load
+  static __device__ __forceinline__ int row(int i, int tid) { return (i * NT + tid) / CPR; }
+  static __device__ __forceinline__ int col8(int i, int tid) {
+    const int q = i * NT + tid;
+    return ((q % CPR) ^ ((q / CPR) & (CPR - 1))) * 8;
+  }
   __device__ __forceinline__ void init(int64_t kst, int tid) {
 #pragma unroll
-    for (int i = 0; i < NLOAD; ++i) {
-      const int q = i * NT + tid;
-      const int r = q / CPR, cp = q % CPR;
-      row[i] = r;
-      col8[i] = (cp ^ (r & (CPR - 1))) * 8;
-      src_off[i] = (uint32_t)(((int64_t)r * kst + col8[i]) * 2);
-    }
+    for (int i = 0; i < NLOAD; ++i) src_off[i] = (uint32_t)(((int64_t)row(i, tid) * kst + col8(i, tid)) * 2);
   }
 };
 
@@ -85,17 +83,23 @@ __device__ __forceinline__ void issue_tile_loads_impl(const TilePieces<D, NT>& t
   const int wave_slot0 = __builtin_amdgcn_readfirstlane(tid) & ~63;
   if (wave_slot0 >= NT) return;                         // not a loading wavefront (wave-uniform)
   const char* tile_base = reinterpret_cast<const char*>(kg + (int64_t)key0 * kst);   // uniform
+  if (FULL) {
 #pragma unroll
-  for (int i = 0; i < NLOAD; ++i) {
-    {
-      const char* src;
-      if (FULL) {
-        src = tile_base + tp.src_off[i];
-      } else {                                            // last, partial tile: clamp the row
-        const int key = min(key0 + tp.row[i], N - 1);
-        src = reinterpret_cast<const char*>(kg + (int64_t)key * kst + tp.col8[i]);
-      }
+    for (int i = 0; i < NLOAD; ++i) {
+      const char* src = tile_base + tp.src_off[i];
       __bf16* dst = lds_buf + (int64_t)(i * NT + wave_slot0) * 8;     // wave-uniform base
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
+                                       (__attribute__((address_space(3))) void*)dst, 16, 0, 0);
+    }
+  } else {
+    // last, partial tile of a head: rows past N - 1 read key N - 1 instead.  Kept as a loop (it runs
+    // once per head and launch; unrolled it would hold NLOAD row addresses in registers all along)
+    const int last = N - 1 - key0;                        // last valid row of the tile
+#pragma unroll 1
+    for (int i = 0; i < NLOAD; ++i) {
+      const int r = min(TilePieces<D, NT>::row(i, tid), last);
+      const char* src = tile_base + ((int64_t)r * kst + TilePieces<D, NT>::col8(i, tid)) * 2;
+      __bf16* dst = lds_buf + (int64_t)(i * NT + wave_slot0) * 8;
       __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
                                        (__attribute__((address_space(3))) void*)dst, 16, 0, 0);
     }
@@ -137,17 +141,23 @@ constexpr int tile_loads_per_wave() { return (KT * (D / 8)) / NT; }
 // Top-of-iteration wait: the current tile must have landed.  `younger` = tiles issued after it that
 // are still in flight (at most STAGES-2).  With a uniform per-wave load count those may stay
 // outstanding; otherwise wait for everything.
+template <int L, int Y>
+__device__ __forceinline__ void wait_younger(int younger) {
+  if constexpr (Y == 0) {
+    wait_vmem<0>();
+  } else {
+    if (younger >= Y) wait_vmem<Y * L>();
+    else wait_younger<L, Y - 1>(younger);
+  }
+}
 template <int D, int NT, int STAGES>
 __device__ __forceinline__ void wait_tile(int younger) {
   constexpr int L = tile_loads_per_wave<D, NT>();
-  static_assert(STAGES >= 2 && STAGES <= 6, "ring depth");
-  if constexpr (L > 0 && L * (STAGES - 2) < 64) {
-    if (STAGES >= 6 && younger >= 4) return wait_vmem<(STAGES >= 6 ? 4 : 0) * L>();
-    if (STAGES >= 5 && younger >= 3) return wait_vmem<(STAGES >= 5 ? 3 : 0) * L>();
-    if (STAGES >= 4 && younger >= 2) return wait_vmem<(STAGES >= 4 ? 2 : 0) * L>();
-    if (STAGES >= 3 && younger >= 1) return wait_vmem<(STAGES >= 3 ? 1 : 0) * L>();
-  }
-  wait_vmem<0>();
+  static_assert(STAGES >= 2, "ring depth");
+  if constexpr (L > 0 && L * (STAGES - 2) < 64)
+    wait_younger<L, STAGES - 2>(younger);
+  else
+    wait_vmem<0>();
 }
 
 // K fragment of kstep ks for the 32-key sub-tile `sub`: lane (ln, half) holds key ln,
@@ -246,6 +256,34 @@ __device__ __forceinline__ ChunkRange chunk_range(int chunk, int g, int Hk, int 
 // (inputs are finite or -inf here).
 __device__ __forceinline__ float max2(float a, float b) { return __builtin_fmaxf(a, b); }
 
+// Fold the logits of one 32-key sub-tile (keys on the accumulator's register axis; `key_lo` = key of
+// this lane's register 0) into the running (max, sum) of the lane's query row, per row block.
+template <int RB>
+__device__ __forceinline__ void rowstats_fold(const f32x16 (&acc)[RB], bool need_mask, int key_lo, int N, int T,
+                                              const int (&wi)[RB], float c1, float (&m_run)[RB], float (&z_run)[RB]) {
+#pragma unroll
+  for (int rb = 0; rb < RB; ++rb) {
+    float x[16];
+#pragma unroll
+    for (int r = 0; r < 16; ++r) x[r] = acc[rb][r];
+    if (need_mask) {
+      // visible iff key < N and (key < T or key - T <= wi)  <=>  key < min(N, T + wi + 1)
+      const int lim = min(N, T + wi[rb] + 1) - key_lo;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) x[r] = (8 * (r >> 2) + (r & 3) < lim) ? x[r] : -INFINITY;
+    }
+    float mx = x[0];
+#pragma unroll
+    for (int r = 1; r < 16; r += 2) mx = max2(mx, max2(x[r], x[(r + 1) & 15]));
+    const float m_new = max2(m_run[rb], mx * c1);
+    float sum = 0.f;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) sum += fast_exp2(fmaf(x[r], c1, -m_new));
+    z_run[rb] = z_run[rb] * fast_exp2(m_run[rb] - m_new) + sum;
+    m_run[rb] = m_new;
+  }
+}
+
 // One tile of pass 1: start the next tile's LDS-direct loads into `nxt`, then fold the tile in
 // `cur` into the running (max, sum).  The two LDS buffers are distinct restrict pointers so that
 // the compiler knows the fragment reads of `cur` need not wait for the loads into `nxt`.
@@ -271,27 +309,7 @@ __device__ __forceinline__ void rowstats_tile(const __bf16* __restrict__ cur, __
 #pragma unroll
       for (int rb = 0; rb < RB; ++rb) nxt_acc[rb] = acc[rb];
     }
-#pragma unroll
-    for (int rb = 0; rb < RB; ++rb) {
-      float x[16];
-#pragma unroll
-      for (int r = 0; r < 16; ++r) x[r] = acc[rb][r];
-      if (need_mask) {
-        // visible iff key < N and (key < T or key - T <= wi)  <=>  key < min(N, T + wi + 1)
-        const int lim = min(N, T + wi[rb] + 1) - (kbase + sub * 32 + 4 * half);
-#pragma unroll
-        for (int r = 0; r < 16; ++r) x[r] = (8 * (r >> 2) + (r & 3) < lim) ? x[r] : -INFINITY;
-      }
-      float mx = x[0];
-#pragma unroll
-      for (int r = 1; r < 16; r += 2) mx = max2(mx, max2(x[r], x[(r + 1) & 15]));
-      const float m_new = max2(m_run[rb], mx * c1);
-      float sum = 0.f;
-#pragma unroll
-      for (int r = 0; r < 16; ++r) sum += fast_exp2(fmaf(x[r], c1, -m_new));
-      z_run[rb] = z_run[rb] * fast_exp2(m_run[rb] - m_new) + sum;
-      m_run[rb] = m_new;
-    }
+    rowstats_fold<RB>(acc, need_mask, kbase + sub * 32 + 4 * half, N, T, wi, c1, m_run, z_run);
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) acc[rb] = nxt_acc[rb];
   }
@@ -367,9 +385,9 @@ score_rowstats_kernel(const __bf16* __restrict__ q_obs, const __bf16* __restrict
 // second chunk, in chunk order with a running maximum; the two halves are added in a fixed order,
 // so every caller gets the same bits for the same partials.
 // p points at the row's partial of chunk 0; consecutive chunks are M float2 apart.
+// Batches of kB chunks per lane: all loads of a batch are issued before the first is used.
+template <int kB = 48>
 __device__ __forceinline__ float combine_row(const float2* __restrict__ p, int M, int n_chunks, int half) {
-  // batches of kB chunks per lane: all loads of a batch are issued before the first is used
-  constexpr int kB = 48;
   float m = kNegBig, z = 0.f;
   for (int c0 = half; c0 < n_chunks; c0 += 2 * kB) {
     float2 v[kB];
@@ -412,6 +430,18 @@ score_combine_kernel(const float* __restrict__ row_part, int Hk, int M, int n_ch
   }
 }
 
+// This lane's share of the column sums of one 32-key sub-tile (query rows on the accumulator's
+// register axis): the normalised probabilities of its 16 rows per block, added in a fixed order.
+template <int RB>
+__device__ __forceinline__ float colsum_fold(const f32x16 (&acc)[RB], const float (&rc)[RB][16], float c1) {
+  float cs = 0.f;
+#pragma unroll
+  for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) cs += fast_exp2(fmaf(acc[rb][r], c1, -rc[rb][r]));
+  return cs;
+}
+
 // One tile of pass 2: start the next tile's loads into `nxt`, then the column partial sums of
 // this wave's 32*RB rows for the KT keys in `cur` (written to red_w[0..KT-1]).
 template <int D, int NT, int RB>
@@ -432,11 +462,7 @@ __device__ __forceinline__ void colsum_tile(const __bf16* __restrict__ cur, __bf
 #pragma unroll
       for (int rb = 0; rb < RB; ++rb) nxt_acc[rb] = acc[rb];
     }
-    float cs = 0.f;
-#pragma unroll
-    for (int rb = 0; rb < RB; ++rb)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) cs += fast_exp2(fmaf(acc[rb][r], c1, -rc[rb][r]));
+    const float cs = colsum_fold<RB>(acc, rc, c1);
     const float other = __shfl_xor(cs, 32);
     if (half == 0) red_w[sub * 32 + ln] = cs + other;
 #pragma unroll
@@ -638,9 +664,9 @@ static int score_chunks(const asl_params& p, int resident) {
 
 // Workgroups of `kernel` that fit on one compute unit at once (registers, LDS, wave slots).
 template <typename K>
-static int resident_per_cu(K kernel, int threads) {
+static int resident_per_cu(K kernel, int threads, size_t dynamic_lds = 0) {
   int n = 0;
-  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, kernel, threads, 0) != hipSuccess || n < 1) {
+  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, kernel, threads, dynamic_lds) != hipSuccess || n < 1) {
     (void)hipGetLastError();
     n = 1;
   }
