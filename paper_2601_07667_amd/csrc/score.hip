@@ -119,11 +119,15 @@ __device__ __forceinline__ void issue_tile_loads(const TilePieces<D, NT>& tp, co
 
 // Wait until at most CNT of this wave's vector-memory operations (incl. its LDS-direct loads) are
 // still outstanding; they complete in issue order, so everything older than the last CNT is done.
+// The same instruction waits for all of the wave's LDS operations (lgkmcnt 0): every use of it is
+// followed by the workgroup barrier that hands this wave's LDS writes (pass 2's column partials) to
+// other waves, and the wait the compiler derives from the barrier's fence was seen to disappear next
+// to this hand-written one (the partials of a tile's last sub-tile were then read before they landed).
 template <int CNT>
 __device__ __forceinline__ void wait_vmem() {
   static_assert(CNT >= 0 && CNT < 64, "vmcnt is a 6-bit count");
-  // vmcnt(CNT): low 4 bits in [3:0], high 2 bits in [15:14]; expcnt / lgkmcnt left at "no wait"
-  __builtin_amdgcn_s_waitcnt(0x0F70 | (CNT & 0xF) | ((CNT >> 4) << 14));
+  // vmcnt(CNT): low 4 bits in [3:0], high 2 bits in [15:14]; expcnt [6:4] left at "no wait"; lgkmcnt [11:8] = 0
+  __builtin_amdgcn_s_waitcnt(0x0070 | (CNT & 0xF) | ((CNT >> 4) << 14));
 }
 
 // Threads of an NW-wavefront workgroup that load the K tiles.

@@ -27,10 +27,13 @@ __global__ void __launch_bounds__(kFinThreads) select_guess_kernel(SelectArgs a)
   select_guess_body(sh, a, (int)blockIdx.x);
 }
 
-// grid: x = tile, y = row
-__global__ void __launch_bounds__(kFilterThreads) select_filter_kernel(SelectArgs a) {
+// grid: x = tile, y = row.  Small workgroups when there are enough tiles to fill the device several
+// times over (a workgroup lives ~5 us whatever its size: more of them in flight stream faster), large
+// ones for a few rows (one round of workgroups: the shorter each one's share, the sooner it ends).
+template <int NT, bool VEC>
+__global__ void __launch_bounds__(NT) select_filter_kernel(SelectArgs a) {
   __shared__ FilterShared sh;
-  select_filter_body<kFilterThreads>(sh, a, (int)blockIdx.y, (int)blockIdx.x);
+  select_filter_body<NT, VEC>(sh, a, (int)blockIdx.y, (int)blockIdx.x);
 }
 
 // dynamic LDS: kFinishLdsBytes
@@ -69,7 +72,18 @@ hipError_t launch_select(const Workspace& ws, const float* scores, int rows, int
     const int nr = rows - row0 < rows_per_round ? rows - row0 : rows_per_round;
     const SelectArgs a = select_args(ws, scores + (int64_t)row0 * T, T, k, W, idx_out + (int64_t)row0 * (k + W), false);
     ASL_LAUNCH(ws.prof, kKernSelHist, st, select_guess_kernel, dim3(nr), dim3(kFinThreads), 0, st, a);
-    ASL_LAUNCH(ws.prof, kKernSelHist, st, select_filter_kernel, dim3(a.n_tiles, nr), dim3(kFilterThreads), 0, st, a);
+    // rows that start on 16-byte boundaries are read four scores at a time
+    const bool vec = (T % 4 == 0) && (reinterpret_cast<uintptr_t>(a.scores) % 16 == 0);
+    const bool small = (long)a.n_tiles * nr >= kFilterSmallFrom;
+    const dim3 fgrid(a.n_tiles, nr);
+    if (small && vec)
+      ASL_LAUNCH(ws.prof, kKernSelHist, st, (select_filter_kernel<kFilterThreads, true>), fgrid, dim3(kFilterThreads), 0, st, a);
+    else if (small)
+      ASL_LAUNCH(ws.prof, kKernSelHist, st, (select_filter_kernel<kFilterThreads, false>), fgrid, dim3(kFilterThreads), 0, st, a);
+    else if (vec)
+      ASL_LAUNCH(ws.prof, kKernSelHist, st, (select_filter_kernel<kFinThreads, true>), fgrid, dim3(kFinThreads), 0, st, a);
+    else
+      ASL_LAUNCH(ws.prof, kKernSelHist, st, (select_filter_kernel<kFinThreads, false>), fgrid, dim3(kFinThreads), 0, st, a);
     ASL_LAUNCH(ws.prof, kKernSelWrite, st, select_finish_kernel, dim3(nr), dim3(kFinThreads), kFinishLdsBytes, st, a);
   }
   return hipGetLastError();

@@ -8,7 +8,8 @@ namespace asl {
 constexpr int kFinThreads = 1024;                      // workgroup of all three kernels
 constexpr int kFinWaves = kFinThreads / 64;
 constexpr int kFinPerThread = 8;                       // consecutive elements per thread in the ordered write
-constexpr int kFilterThreads = 256;                    // filter workgroup when it runs as its own launch
+constexpr int kFilterThreads = 256;                    // filter workgroup of its own launch over many tiles ...
+constexpr int kFilterSmallFrom = 2048;                 // ... (rows x tiles per row) from this many on; kFinThreads below
 constexpr uint32_t kSegOverflow = 0xffffffffu;         // a tile's count when its segment was too small
 static_assert(kSelTile % kFinThreads == 0 && kSelTile % kFilterThreads == 0, "filter tile geometry");
 
@@ -191,25 +192,47 @@ struct FilterShared {
 
 // Step 2: the tile's keys <= bound, in token order, to the tile's segment of the candidate buffer.
 // NT threads per workgroup: each wavefront takes kSelTile / (NT / 64) consecutive tokens.
-template <int NT>
+// VEC: a lane reads four neighbouring scores with one 16-byte load (the row must start on a 16-byte
+// boundary: T % 4 == 0 and an aligned base); otherwise one score per load.
+template <int NT, bool VEC>
 __device__ __forceinline__ void select_filter_body(FilterShared& sh, const SelectArgs& a, int row, int tile) {
-  constexpr int kWaves = NT / 64, kSelPerWave = kSelTile / kWaves, kSelRounds = kSelPerWave / 64;
+  constexpr int kWaves = NT / 64, kSelPerWave = kSelTile / kWaves;
+  constexpr int kPer = VEC ? 4 : 1;                     // neighbouring tokens per lane and round
+  constexpr int kSelRounds = kSelPerWave / (64 * kPer);
+  static_assert(kSelRounds >= 1, "filter tile geometry");
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, T = a.T;
   const float* sr = a.scores + (int64_t)row * T;
   const int base = tile * kSelTile + wave * kSelPerWave;
-  uint32_t key[kSelRounds];
+  uint32_t key[kSelRounds][kPer];
 #pragma unroll
   for (int r = 0; r < kSelRounds; ++r) {               // all loads in flight before the first use
-    const int e = base + r * 64 + lane;
-    key[r] = (e < T) ? order_key(sr[e]) : 0u;
+    const int e = base + (r * 64 + lane) * kPer;
+    if (VEC) {
+      float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (e + 3 < T) {
+        v = *reinterpret_cast<const float4*>(sr + e);
+      } else {                                          // the row's last, partial piece
+        if (e < T) v.x = sr[e];
+        if (e + 1 < T) v.y = sr[e + 1];
+        if (e + 2 < T) v.z = sr[e + 2];
+      }
+      key[r][0] = order_key(v.x);
+      key[r][1 % kPer] = order_key(v.y);
+      key[r][2 % kPer] = order_key(v.z);
+      key[r][3 % kPer] = order_key(v.w);
+    } else {
+      key[r][0] = (e < T) ? order_key(sr[e]) : 0u;
+    }
   }
   const uint32_t b = a.bound[row];
   uint32_t w_cnt = 0;
 #pragma unroll
-  for (int r = 0; r < kSelRounds; ++r) {
-    const bool keep = (base + r * 64 + lane < T) && key[r] <= b;
-    w_cnt += __popcll(__ballot(keep));
-  }
+  for (int r = 0; r < kSelRounds; ++r)
+#pragma unroll
+    for (int j = 0; j < kPer; ++j) {
+      const bool keep = (base + (r * 64 + lane) * kPer + j < T) && key[r][j] <= b;
+      w_cnt += __popcll(__ballot(keep));
+    }
   if (lane == 0) sh.wave_tot[wave] = w_cnt;
   __syncthreads();
   uint32_t run = 0, total = 0;
@@ -225,15 +248,27 @@ __device__ __forceinline__ void select_filter_body(FilterShared& sh, const Selec
   const uint64_t lt_mask = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
 #pragma unroll
   for (int r = 0; r < kSelRounds; ++r) {
-    const int e = base + r * 64 + lane;
-    const bool keep = (e < T) && key[r] <= b;
-    const uint64_t bal = __ballot(keep);
-    if (keep) {
-      const uint32_t pos = run + (uint32_t)__popcll(bal & lt_mask);
-      ck[pos] = key[r];
-      ci[pos] = (uint32_t)e;
+    const int e0 = base + (r * 64 + lane) * kPer;
+    // token order inside a round: lane by lane, a lane's kPer tokens in a row
+    bool keep[kPer];
+    uint32_t before = 0, round_tot = 0;                 // kept by lower lanes / by the whole wavefront
+#pragma unroll
+    for (int j = 0; j < kPer; ++j) {
+      keep[j] = (e0 + j < T) && key[r][j] <= b;
+      const uint64_t bal = __ballot(keep[j]);
+      before += (uint32_t)__popcll(bal & lt_mask);
+      round_tot += (uint32_t)__popcll(bal);
     }
-    run += (uint32_t)__popcll(bal);
+    uint32_t pos = run + before;
+#pragma unroll
+    for (int j = 0; j < kPer; ++j) {
+      if (keep[j]) {
+        ck[pos] = key[r][j];
+        ci[pos] = (uint32_t)(e0 + j);
+        ++pos;
+      }
+    }
+    run += round_tot;
   }
 }
 

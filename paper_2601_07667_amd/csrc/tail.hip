@@ -49,7 +49,7 @@ __global__ void __launch_bounds__(kTailThreads) tail1_kernel(SortArgs sa, Select
     sort_pass_body<R, false, false>(sh.sort, sa, b);
   } else {
     const int j = b - sa.n_tiles;
-    select_filter_body<kTailThreads>(sh.filter, se, j / se.n_tiles, j % se.n_tiles);
+    select_filter_body<kTailThreads, false>(sh.filter, se, j / se.n_tiles, j % se.n_tiles);
   }
 }
 

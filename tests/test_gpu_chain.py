@@ -343,9 +343,14 @@ def _layer_step_case(dev, L, layer_idx=0):
     ctx.asl_select_topk(p, s2, 1, Ia)
     ctx.asl_gather_kv(p, kd, vd, Ih, sh.Hk, n_idx, K2, V2)
     torch.cuda.synchronize()
-    assert torch.equal(scores[:sh.Hk], P2) and torch.equal(scores[sh.Hk], s2)
-    assert torch.equal(ring, ring2) and torch.equal(I[:sh.Hk], Ih) and torch.equal(I[sh.Hk:], Ia)
-    assert torch.equal(Kc, K2) and torch.equal(Vc, V2) and torch.equal(state, state2) 
+    for what, a, b in (("P", scores[:sh.Hk], P2), ("s", scores[sh.Hk], s2), ("rank ring", ring, ring2),
+                       ("per-head indices", I[:sh.Hk], Ih), ("all-head indices", I[sh.Hk:], Ia), ("K[I]", Kc, K2),
+                       ("V[I]", Vc, V2), ("state", state, state2)):
+        if not torch.equal(a, b):
+            d = torch.nonzero(a.reshape(-1) != b.reshape(-1)).reshape(-1)
+            raise AssertionError(f"{L.name}: {what} of asl_layer_step differs from the single calls at {d.numel()} of "
+                                 f"{a.numel()} places, first at flat index {int(d[0])}: {a.reshape(-1)[d[0]].item()} vs "
+                                 f"{b.reshape(-1)[d[0]].item()}; fault word {ctx.asl_device_fault()}")
     out = dict(P=scores[:sh.Hk].cpu().numpy(), s=scores[sh.Hk].cpu().numpy(),
                rank=ring[layer_idx % sh.L_obs].cpu().numpy().astype(np.int64),
                stat=asl.read_struct(stat, asl.AslStat), I_head=I[:sh.Hk].cpu().numpy().astype(np.int64),

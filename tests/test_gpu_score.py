@@ -231,3 +231,34 @@ def test_row_counts_up_to_512(gpu_device, Hq, Hk, W):
     blocks, with and without padded rows."""
     _compare(gpu_device, _small(Hq, Hk, 128, 3000 + 13 * Hq, W, seed=30 + Hq))
     _compare(gpu_device, _small(Hq, Hk, 64, 1500 + 7 * Hq, W, seed=40 + Hq))
+
+
+@pytest.mark.parametrize("Hq,Hk,W,N,reps", [(32, 8, 32, 131072, 300), (16, 4, 64, 65536, 200), (8, 4, 32, 40000, 200),
+                                            (14, 2, 32, 50000, 200)])
+def test_scoring_is_reproducible(gpu_device, Hq, Hk, W, N, reps):
+    """The same call on the same inputs gives the same bits every time (all reductions have a fixed
+    order), with another key tensor scored in between.  Regression test: a missing wait for the LDS
+    writes of pass 2's column partials once made one 32-key sub-tile differ in a few runs per hundred."""
+    import torch
+    dev = gpu_device
+    torch.manual_seed(Hq * 1000 + W)
+    ctx = asl.Asl(N, Hk, Hq * W)
+    p = asl.make_params(Hq, Hk, 128, N, W, 7, 2048)
+    q = torch.randn(Hq, W, 128, device=dev).to(torch.bfloat16)
+    k = torch.randn(Hk, N, 128, device=dev).to(torch.bfloat16)
+    other = torch.randn(Hk, N, 128, device=dev).to(torch.bfloat16)
+    P = torch.empty(Hk, N - W, dtype=torch.float32, device=dev)
+    s = torch.empty(N - W, dtype=torch.float32, device=dev)
+    ctx.asl_score_layer(p, q, k, P, s)
+    P0, s0 = P.clone(), s.clone()
+    for i in range(reps):
+        if i % 3 == 0:
+            ctx.asl_score_layer(p, q, other, P, s)
+        P.fill_(-1.0)
+        s.fill_(-1.0)
+        ctx.asl_score_layer(p, q, k, P, s)
+        if not (torch.equal(P, P0) and torch.equal(s, s0)):
+            d = torch.nonzero(P != P0)
+            raise AssertionError(f"run {i} differs from run 0 at {d.shape[0]} places of P, KV heads "
+                                 f"{sorted(set(d[:, 0].tolist()))}, keys {int(d[:, 1].min())}..{int(d[:, 1].max())}")
+    ctx.close()

@@ -218,6 +218,23 @@ def test_rank_select_pool_random_shapes(ctx, gpu_device):
         _select_case(ctx, gpu_device, s, budget, W)
 
 
+@pytest.mark.parametrize("rows,T,budget", [(96, 100000, 1056), (96, 100001, 1056), (300, 9000, 532)])
+def test_select_many_rows(gpu_device, rows, T, budget):
+    """96 rows x 25 tiles: the tile count from which the filter stage runs as many small workgroups
+    (a few rows take one round of large ones); with T a multiple of four the rows are read four scores
+    per load, with T = 100001 one at a time.  300 rows: more than the candidate buffers hold at once,
+    so the three launches run twice."""
+    W = 32
+    rng = np.random.default_rng(rows)
+    s = np.round(rng.random((rows, T), dtype=np.float32), 4).astype(np.float32)
+    c = asl.Asl(T + W, rows, rows * W)
+    try:
+        _select_case(c, gpu_device, s, budget, W)
+        assert c.asl_device_fault() == 0
+    finally:
+        c.close()
+
+
 def test_select_special(ctx, gpu_device):
     T, W = 6000, 16
     _select_case(ctx, gpu_device, np.ones((2, T), dtype=np.float32), 100, W)               # all equal: first k
