@@ -391,6 +391,47 @@ def test_layer_step_at_bench_size_and_beyond(gpu_device):
                      layer_idx=3)
 
 
+def test_layer_step_is_reproducible(gpu_device):
+    """200 repetitions of asl_layer_step on the C3 layer, and of the single ranking and top-k calls on its
+    scores: every output has the same bits every time (the workgroups of the ranking and statistic
+    launches hand counts to each other inside the launch; nothing may depend on who came first)."""
+    import torch
+    dev = gpu_device
+    L = synth.config_layer(3)
+    sh = L.shape
+    ctx = asl.Asl(sh.N, sh.Hk + 1, sh.Hq * sh.W)
+    p = gu.params_of(sh)
+    qd, kd, vd = (gu.to_dev(x, sh.dtype, dev) for x in (L.q_obs, L.k, L.v))
+    T, n_idx = sh.T, sh.k + sh.W
+
+    def step():
+        scores = torch.empty((sh.Hk + 1, T), dtype=torch.float32, device=dev)
+        ring = torch.zeros((sh.L_obs, T), dtype=torch.int32, device=dev)
+        state, stat = asl.new_state(dev), asl.new_stat(dev)
+        I = torch.full((sh.Hk + 1, n_idx), -1, dtype=torch.int32, device=dev)
+        Kc = torch.zeros((sh.Hk, n_idx, sh.d), dtype=kd.dtype, device=dev)
+        Vc = torch.zeros_like(Kc)
+        ctx.asl_layer_step(p, qd, kd, vd, 0, sh.L_min, sh.L_obs, sh.tau, scores, ring, state, stat, I, Kc, Vc)
+        return scores, ring, I, Kc, Vc, stat, state
+
+    def single(scores):
+        ring = torch.zeros((sh.L_obs, T), dtype=torch.int32, device=dev)
+        state, stat = asl.new_state(dev), asl.new_stat(dev)
+        I = torch.full((sh.Hk + 1, n_idx), -1, dtype=torch.int32, device=dev)
+        ctx.asl_rank_stat(p, scores[sh.Hk], 0, sh.L_min, sh.L_obs, sh.tau, ring, state, stat)
+        ctx.asl_select_topk(p, scores, sh.Hk + 1, I)
+        return ring, I, stat, state
+
+    ref = step()
+    ref1 = single(ref[0])
+    for i in range(200):
+        for what, outs, refs in (("asl_layer_step", step(), ref), ("single calls", single(ref[0]), ref1)):
+            for j, (a, b) in enumerate(zip(outs, refs)):
+                assert torch.equal(a, b), f"run {i}: output {j} of {what} differs from the first run"
+    assert ctx.asl_device_fault() == 0
+    ctx.close()
+
+
 def test_second_model_shape_and_large_budget(gpu_device):
     """The 28-layer model's head geometry (4 KV heads, 7 query heads per group: 224 query rows per
     KV head, seven 32-row blocks) and the paper's larger KV budget of 8192."""
