@@ -234,9 +234,10 @@ def main() -> int:
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     tokens_per_s = sh.N / (ms_per_step * 1e-3)
 
-    # Per-kernel durations: HIP events recorded by the library around EVERY kernel, on the stream the
-    # kernel is launched on, in an eager loop of `n_prof` of the same steps right after the timed region
-    # (events cannot bracket single nodes of a replayed graph).
+    # Per-kernel durations: a HIP event pair handed to EVERY kernel launch by the library (the runtime
+    # stamps the pair with the kernel's own start and end on the device, on the stream the kernel is
+    # launched on), in an eager loop of `n_prof` of the same steps right after the timed region (single
+    # nodes of a replayed graph cannot be timed this way).
     n_prof = max(8, min(args.steps, 64))
     ctx.asl_profile_enable((1 << len(asl.KERNEL_NAMES)) - 1, 32 * n_prof)
     layer = next_layer()
@@ -331,11 +332,11 @@ def main() -> int:
                 "unit": "GB/s", "frac": round(dom_gbs / HBM_PEAK_GBS, 4), "traffic": pmc_traffic(args.config, dom),
                 "traffic_source": PMC_TRAFFIC["source"] if pmc_traffic(args.config, dom) else None,
                 "avg_launch_ms": round(dom_avg_ms, 5), "launches": dom_n,
-                "timing": "HIP events recorded by the library around this kernel only, on its launch stream, in an eager "
-                          f"loop of {n_prof} of the same steps after the timed region (the bracket includes the dispatch "
-                          "gap before the kernel, a few microseconds more than the profiler's kernel duration)",
+                "timing": "HIP event pair attached by the library to the launches of this kernel only (hipExtLaunchKernelGGL: "
+                          "stamped with the kernel's start and end on the device, on its launch stream), in an eager loop of "
+                          f"{n_prof} of the same steps after the timed region",
                 "algorithmic_bytes": d_ent["algorithmic_bytes"],
-                "chosen_as": "largest summed duration among the kernels of this run (events around every kernel)",
+                "chosen_as": "largest summed duration among the kernels of this run (event pairs on every launch)",
                 "mfma_tflops": round(useful_flops / (dom_avg_ms * 1e-3) / 1e12, 1) if dom.startswith("score_") else None,
                 "mfma_frac_of_bf16_peak": round(useful_flops / (dom_avg_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4)
                                           if dom.startswith("score_") else None}

@@ -260,8 +260,9 @@ asl_status asl_device_fault(asl_ctx* ctx, int32_t* fault_out);
  * top-k / compaction stages together.  (Each sort pass is one kernel, recorded under 5, id 4 is unused;
  * 8 covers the top-k's bound and filter kernels, 9 its finishing kernel; the statistic is one
  * kernel, 7; 6 is the below-L_min skip.)
- * asl_profile_enable: launches whose id bit is set in kernel_mask are bracketed by HIP events on
- *   the call's stream, up to max_records launches (further ones run unrecorded); mask 0 turns
+ * asl_profile_enable: launches whose id bit is set in kernel_mask carry a HIP event pair that the
+ *   runtime stamps with the kernel's start and end on the device (the call's stream; not under
+ *   stream capture), up to max_records launches (further ones run unrecorded); mask 0 turns
  *   it off and frees the events.  Allocates host memory and events: not for the hot loop.
  * asl_profile_collect: waits for the recorded events of kernel_id and returns their summed
  *   duration in milliseconds and their number; kernel_id -1 clears the records instead. */

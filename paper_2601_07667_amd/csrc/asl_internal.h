@@ -1,6 +1,7 @@
 // Internal declarations shared by the libasl translation units (not part of the C ABI).
 #pragma once
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 #include <stddef.h>
 #include "asl.h"
@@ -23,27 +24,27 @@ struct Prof {
   int* id = nullptr;
 };
 
-// Brackets one launch with a start/stop event pair when its kernel id is enabled.
-struct ProfScope {
-  Prof* p;
-  hipStream_t st;
-  int slot = -1;
-  ProfScope(Prof* prof, int kid, hipStream_t s) : p(prof), st(s) {
-    if (p && ((p->mask >> kid) & 1u) && p->n < p->cap) {
-      slot = p->n++;
-      p->id[slot] = kid;
-      (void)hipEventRecord(p->start[slot], st);
-    }
+// Record slot for one launch of kernel `kid`, or -1 when that kernel is not being timed.
+inline int prof_slot(Prof* p, int kid) {
+  if (p && ((p->mask >> kid) & 1u) && p->n < p->cap) {
+    p->id[p->n] = kid;
+    return p->n++;
   }
-  ~ProfScope() {
-    if (slot >= 0) (void)hipEventRecord(p->stop[slot], st);
-  }
-};
+  return -1;
+}
 
-#define ASL_LAUNCH(prof, kid, st, ...)        \
-  do {                                        \
-    asl::ProfScope ps_((prof), (kid), (st));  \
-    hipLaunchKernelGGL(__VA_ARGS__);          \
+// Launch; a timed launch hands its event pair to the runtime, which stamps them with the kernel's own
+// start and end on the device (events recorded before and after the launch would also measure the
+// dispatch gap in front of the kernel, 3-5 us).
+#define ASL_LAUNCH(prof, kid, st, kernel, grid, block, lds, stream, ...)                                      \
+  do {                                                                                                        \
+    asl::Prof* prof_ = (prof);                                                                                \
+    const int slot_ = asl::prof_slot(prof_, (kid));                                                           \
+    if (slot_ >= 0)                                                                                           \
+      hipExtLaunchKernelGGL(kernel, grid, block, lds, stream, prof_->start[slot_], prof_->stop[slot_], 0,     \
+                            __VA_ARGS__);                                                                     \
+    else                                                                                                      \
+      hipLaunchKernelGGL(kernel, grid, block, lds, stream, __VA_ARGS__);                                      \
   } while (0)
 
 // Workspace carve-up (device memory owned by the ctx).
