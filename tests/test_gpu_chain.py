@@ -374,6 +374,16 @@ def test_layer_step_matches_single_calls_and_oracle(gpu_device):
         _check_layer(L, _layer_step_case(gpu_device, L))
 
 
+@pytest.mark.parametrize("Hq,Hk,d,N,W,S,budget", [(6, 2, 64, 10007, 13, 5, 777), (3, 3, 128, 4099, 7, 3, 64),
+                                                   (8, 1, 128, 33333, 32, 7, 5000), (2, 2, 64, 70, 3, 1, 9)])
+def test_layer_step_ragged_shapes(gpu_device, Hq, Hk, d, N, W, S, budget):
+    """Sizes that are multiples of no tile: odd N and W (score rows that do not start on 16-byte boundaries,
+    ragged last tiles in every kernel), one to three KV heads, a budget above and below one tile."""
+    sh = synth.Shape(Hq=Hq, Hk=Hk, d=d, N=N, W=W, S=S, budget=budget, L_min=0)
+    L = synth.iid_layer(sh, 1000 + N, name=f"ragged-{N}-{W}")
+    _check_layer(L, _layer_step_case(gpu_device, L))
+
+
 def test_layer_step_at_bench_size_and_beyond(gpu_device):
     """asl_layer_step at the size the benchmark times (C3: 64 sort tiles beside the top-k stages) and at
     2^20 tokens (the ranking sort switches to its large tiles): bit-identical to the single calls, and
