@@ -390,31 +390,53 @@ score_rowstats_kernel(const __bf16* __restrict__ q_obs, const __bf16* __restrict
 // so every caller gets the same bits for the same partials.
 // p points at the row's partial of chunk 0; consecutive chunks are M float2 apart.
 // Batches of kB chunks per lane: all loads of a batch are issued before the first is used.
-template <int kB = 48>
-__device__ __forceinline__ float combine_row(const float2* __restrict__ p, int M, int n_chunks, int half) {
-  float m = kNegBig, z = 0.f;
-  for (int c0 = half; c0 < n_chunks; c0 += 2 * kB) {
-    float2 v[kB];
+// NR rows at once (pointers p[0..NR-1]): the loads of a batch go out for all of them before the first
+// is used, so NR rows cost as many memory round trips as one.
+template <int NR, int kB>
+__device__ __forceinline__ void combine_rows(const float2* const (&p)[NR], int M, int n_chunks, int half,
+                                             float (&out)[NR]) {
+  float m[NR], z[NR];
 #pragma unroll
-    for (int j = 0; j < kB; ++j) {
-      const int c = c0 + 2 * j;
-      v[j] = p[(int64_t)min(c, n_chunks - 1) * M];
-      if (c >= n_chunks) v[j] = make_float2(kNegBig, 0.f);
-    }
-    float mb = m;
-#pragma unroll
-    for (int j = 0; j < kB; ++j) mb = fmaxf(mb, v[j].x);
-    float zb = 0.f;
-#pragma unroll
-    for (int j = 0; j < kB; ++j) zb += v[j].y * fast_exp2(v[j].x - mb);
-    z = z * fast_exp2(m - mb) + zb;
-    m = mb;
+  for (int q = 0; q < NR; ++q) {
+    m[q] = kNegBig;
+    z[q] = 0.f;
   }
-  const float mo = __shfl_xor(m, 32), zo = __shfl_xor(z, 32);
-  const float mm = fmaxf(m, mo);
-  const float za = z * fast_exp2(m - mm), zb2 = zo * fast_exp2(mo - mm);
-  const float zs = (half == 0) ? (za + zb2) : (zb2 + za);
-  return mm + log2f(zs);
+  for (int c0 = half; c0 < n_chunks; c0 += 2 * kB) {
+    float2 v[NR][kB];
+#pragma unroll
+    for (int q = 0; q < NR; ++q)
+#pragma unroll
+      for (int j = 0; j < kB; ++j) {
+        const int c = c0 + 2 * j;
+        v[q][j] = p[q][(int64_t)min(c, n_chunks - 1) * M];
+        if (c >= n_chunks) v[q][j] = make_float2(kNegBig, 0.f);
+      }
+#pragma unroll
+    for (int q = 0; q < NR; ++q) {
+      float mb = m[q];
+#pragma unroll
+      for (int j = 0; j < kB; ++j) mb = fmaxf(mb, v[q][j].x);
+      float zb = 0.f;
+#pragma unroll
+      for (int j = 0; j < kB; ++j) zb += v[q][j].y * fast_exp2(v[q][j].x - mb);
+      z[q] = z[q] * fast_exp2(m[q] - mb) + zb;
+      m[q] = mb;
+    }
+  }
+#pragma unroll
+  for (int q = 0; q < NR; ++q) {
+    const float mo = __shfl_xor(m[q], 32), zo = __shfl_xor(z[q], 32);
+    const float mm = fmaxf(m[q], mo);
+    const float za = z[q] * fast_exp2(m[q] - mm), zb2 = zo * fast_exp2(mo - mm);
+    const float zs = (half == 0) ? (za + zb2) : (zb2 + za);
+    out[q] = mm + log2f(zs);
+  }
+}
+__device__ __forceinline__ float combine_row(const float2* __restrict__ p, int M, int n_chunks, int half) {
+  const float2* const ps[1] = {p};
+  float out[1];
+  combine_rows<1, 48>(ps, M, n_chunks, half, out);
+  return out[0];
 }
 
 // The offsets of all Hk*M rows (one wavefront per 32 rows), for callers that want the rows'
@@ -513,19 +535,24 @@ score_colsum_kernel(const __bf16* __restrict__ q_obs, const __bf16* __restrict__
   // Log2-domain softmax offsets of this lane's accumulator rows: from the caller's log-sum-exp
   // (row_const, scaled by rc_mul), or folded here from pass 1's per-chunk partials (row_part).
   float rc[RB][16];
+  float mine[RB];                                       // offsets of rows  row0 + 32*rb + ln
+#pragma unroll
+  for (int rb = 0; rb < RB; ++rb) mine[rb] = 0.f;
+  if (row_part != nullptr) {
+    const float2* ps[RB];
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb)
+      ps[rb] = reinterpret_cast<const float2*>(row_part) + (int64_t)g * n_parts * M + min(row0 + rb * 32 + ln, M - 1);
+    combine_rows<RB, (RB == 1 ? 48 : 32)>(reinterpret_cast<const float2* const (&)[RB]>(ps), M, n_parts, half, mine);
+  }
 #pragma unroll
   for (int rb = 0; rb < RB; ++rb) {
-    float mine = 0.f;                                   // offset of row  row0 + 32*rb + ln
-    if (row_part != nullptr) {
-      const int qr = min(row0 + rb * 32 + ln, M - 1);
-      mine = combine_row(reinterpret_cast<const float2*>(row_part) + (int64_t)g * n_parts * M + qr, M, n_parts, half);
-    }
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
       const int row = row0 + rb * 32 + acc_row(r, half);
       float v;
       if (row_part != nullptr)
-        v = __shfl(mine, acc_row(r, half));             // lanes 0..31 hold rows 0..31 of the block
+        v = __shfl(mine[rb], acc_row(r, half));         // lanes 0..31 hold rows 0..31 of the block
       else
         v = row_const[(int64_t)g * M + min(row, M - 1)] * rc_mul;
       rc[rb][r] = (row < M) ? v : INFINITY;              // padded rows add 2^-inf = 0
