@@ -345,13 +345,46 @@ __device__ __forceinline__ int finish_load(FinishShared& sh, uint32_t* lds_cand,
   if (sh.whole_row) return 0;                          // uniform
   uint32_t* lk = lds_cand;
   uint32_t* li = lds_cand + kSelCandCap;
-  // wavefront w copies tiles w, w + kFinWaves, ...
-  for (int t = tid >> 6; t < n_tiles; t += kFinWaves) {
-    const uint32_t o = sh.seg_off[t], c = sh.seg_off[t + 1] - o;
-    const int64_t seg = ((int64_t)row * n_tiles + t) * kSelSegment;
-    for (uint32_t j = tid & 63; j < c; j += 64) {
-      lk[o + j] = a.cand_key[seg + j];
-      li[o + j] = a.cand_idx[seg + j];
+  // Wavefront w copies tiles w, w + kFinWaves, ..., two tiles and 128 candidates of each at a time:
+  // the eight loads of such a step are in flight together (a tile holds ~100 candidates at the
+  // usual budgets, so a row takes one memory round trip instead of one per tile and 64 candidates).
+  const int lane = tid & 63;
+  for (int t0 = tid >> 6; t0 < n_tiles; t0 += 2 * kFinWaves) {
+    uint32_t o[2], c[2];
+    int64_t seg[2];
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+      const int t = t0 + q * kFinWaves;
+      const bool in = t < n_tiles;
+      o[q] = in ? sh.seg_off[t] : 0u;
+      c[q] = in ? sh.seg_off[t + 1] - o[q] : 0u;
+      seg[q] = ((int64_t)row * n_tiles + (in ? t : 0)) * kSelSegment;
+    }
+    const uint32_t c_max = c[0] > c[1] ? c[0] : c[1];
+    for (uint32_t j0 = 0; j0 < c_max; j0 += 128) {
+      uint32_t kk[2][2], ii[2][2];
+#pragma unroll
+      for (int q = 0; q < 2; ++q)
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+          const uint32_t j = j0 + u * 64 + lane;
+          kk[q][u] = 0;
+          ii[q][u] = 0;
+          if (j < c[q]) {
+            kk[q][u] = a.cand_key[seg[q] + j];
+            ii[q][u] = a.cand_idx[seg[q] + j];
+          }
+        }
+#pragma unroll
+      for (int q = 0; q < 2; ++q)
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+          const uint32_t j = j0 + u * 64 + lane;
+          if (j < c[q]) {
+            lk[o[q] + j] = kk[q][u];
+            li[o[q] + j] = ii[q][u];
+          }
+        }
     }
   }
   __syncthreads();
