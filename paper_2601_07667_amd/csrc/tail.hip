@@ -40,8 +40,9 @@ __global__ void __launch_bounds__(kTailThreads) tail0_kernel(SortArgs sa, Select
     select_guess_body(sh.guess, se, b - sa.n_tiles);
 }
 
-// launch 1: sort pass 1 | top-k filter (one workgroup per tile of a score row)
-template <int R>
+// launch 1: sort pass 1 | top-k filter (one workgroup per tile of a score row; VEC: 16-byte loads,
+// for rows that start on 16-byte boundaries)
+template <int R, bool VEC>
 __global__ void __launch_bounds__(kTailThreads) tail1_kernel(SortArgs sa, SelectArgs se) {
   __shared__ SortFilterShared sh;
   const int b = (int)blockIdx.x;
@@ -49,7 +50,7 @@ __global__ void __launch_bounds__(kTailThreads) tail1_kernel(SortArgs sa, Select
     sort_pass_body<R, false, false>(sh.sort, sa, b);
   } else {
     const int j = b - sa.n_tiles;
-    select_filter_body<kTailThreads, false>(sh.filter, se, j / se.n_tiles, j % se.n_tiles);
+    select_filter_body<kTailThreads, VEC>(sh.filter, se, j / se.n_tiles, j % se.n_tiles);
   }
 }
 
@@ -105,7 +106,8 @@ static int tail_max_tiles() {
     (void)hipFuncSetAttribute(reinterpret_cast<const void*>(tail3_kernel<R>), hipFuncAttributeMaxDynamicSharedMemorySize,
                               (int)kSortFinishLdsBytes);
     int m = kSortMaxTiles;
-    const int c[] = {coresident_limit(tail0_kernel<R>, kTailThreads), coresident_limit(tail1_kernel<R>, kTailThreads),
+    const int c[] = {coresident_limit(tail0_kernel<R>, kTailThreads), coresident_limit(tail1_kernel<R, false>, kTailThreads),
+                     coresident_limit(tail1_kernel<R, true>, kTailThreads),
                      coresident_limit(tail2_kernel<R>, kTailThreads, 1024, kSortFinishLdsBytes),
                      coresident_limit(tail3_kernel<R>, kTailThreads, 1024, kSortFinishLdsBytes)};
     for (int v : c) m = v < m ? v : m;
@@ -123,8 +125,12 @@ static hipError_t launch_tail_r(const Workspace& ws, const float* scores, int ro
   const dim3 block(kTailThreads);
   ASL_LAUNCH(ws.prof, kKernTail, st, (tail0_kernel<R>), dim3(n_tiles + rows), block, 0, st,
              sort_pass_args(ws, s_all, T, n_tiles, rank_row, 0), se);
-  ASL_LAUNCH(ws.prof, kKernTail, st, (tail1_kernel<R>), dim3(n_tiles + rows * se.n_tiles), block, 0, st,
-             sort_pass_args(ws, s_all, T, n_tiles, rank_row, 1), se);
+  if (T % 4 == 0 && reinterpret_cast<uintptr_t>(scores) % 16 == 0)
+    ASL_LAUNCH(ws.prof, kKernTail, st, (tail1_kernel<R, true>), dim3(n_tiles + rows * se.n_tiles), block, 0, st,
+               sort_pass_args(ws, s_all, T, n_tiles, rank_row, 1), se);
+  else
+    ASL_LAUNCH(ws.prof, kKernTail, st, (tail1_kernel<R, false>), dim3(n_tiles + rows * se.n_tiles), block, 0, st,
+               sort_pass_args(ws, s_all, T, n_tiles, rank_row, 1), se);
   ASL_LAUNCH(ws.prof, kKernTail, st, (tail2_kernel<R>), dim3(n_tiles + rows), block, kSortFinishLdsBytes, st,
              sort_pass_args(ws, s_all, T, n_tiles, rank_row, 2), se);
   ASL_LAUNCH(ws.prof, kKernTail, st, (tail3_kernel<R>), dim3(n_tiles + rows), block, kSortFinishLdsBytes, st,
