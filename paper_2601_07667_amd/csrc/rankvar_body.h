@@ -6,6 +6,8 @@
 namespace asl {
 
 constexpr int kVarThreads = 256;
+constexpr int kVarTok = 2;                  // tokens per thread whose ranks are in flight together ...
+constexpr int kVarRowBatch = 8;             // ... and ring rows of each
 
 // The ring row of layer_idx continues the rows already held iff layer_idx is the layer after
 // state->last_layer, or that layer minus l_obs (a captured trip of l_obs layers round the ring being
@@ -60,21 +62,50 @@ __device__ __forceinline__ void rankvar_body(RankvarShared& sh, const RankvarArg
   if (n >= 2) {
     int row0 = (a.layer_idx - (n - 1)) % a.l_obs;            // oldest row in use
     if (row0 < 0) row0 += a.l_obs;
-    for (int t = block * kVarThreads + tid; t < a.T; t += n_blocks * kVarThreads) {
-      unsigned long long s1 = 0, s2 = 0;
-      int mn = 0x7fffffff;
-      int row = row0;
-#pragma unroll 8
-      for (int j = 0; j < n; ++j) {
-        const int r = a.ring[(int64_t)row * a.T + t];
-        row = (row + 1 == a.l_obs) ? 0 : row + 1;
-        s1 += (unsigned long long)r;
-        s2 += (unsigned long long)r * (unsigned long long)r;
-        mn = r < mn ? r : mn;
+    // kVarTok tokens per thread and kVarRowBatch rows of each are read together: the loads of such a
+    // step are issued before any is waited for, whatever n is (rows beyond n and tokens beyond T
+    // re-read a valid element and are left out of the sums).
+    const int stride = n_blocks * kVarThreads;
+    for (int t0 = block * kVarThreads + tid; t0 < a.T; t0 += kVarTok * stride) {
+      unsigned long long s1[kVarTok], s2[kVarTok];
+      int mn[kVarTok];
+#pragma unroll
+      for (int q = 0; q < kVarTok; ++q) {
+        s1[q] = 0;
+        s2[q] = 0;
+        mn[q] = 0x7fffffff;
       }
-      if (mn < a.k) {
-        num += (unsigned long long)n * s2 - s1 * s1;
-        cnt += 1;
+      for (int j0 = 0; j0 < n; j0 += kVarRowBatch) {
+        int r[kVarTok][kVarRowBatch];
+#pragma unroll
+        for (int u = 0; u < kVarRowBatch; ++u) {
+          int row = row0 + ((j0 + u < n) ? j0 + u : 0);          // < 2 l_obs
+          row = (row >= a.l_obs) ? row - a.l_obs : row;
+#pragma unroll
+          for (int q = 0; q < kVarTok; ++q) {
+            const int t = t0 + q * stride;
+            r[q][u] = a.ring[(int64_t)row * a.T + (t < a.T ? t : t0)];
+          }
+        }
+#pragma unroll
+        for (int u = 0; u < kVarRowBatch; ++u) {
+          const int keep = (j0 + u < n) ? -1 : 0;                // all ones or zero, uniform; no branch, so
+#pragma unroll                                                   // that every load above stays unconditional
+          for (int q = 0; q < kVarTok; ++q) {
+            const int v = r[q][u] & keep;                        // ranks are >= 0
+            const int vm = r[q][u] | (~keep & 0x7fffffff);
+            s1[q] += (unsigned long long)v;
+            s2[q] += (unsigned long long)v * (unsigned long long)v;
+            mn[q] = vm < mn[q] ? vm : mn[q];
+          }
+        }
+      }
+#pragma unroll
+      for (int q = 0; q < kVarTok; ++q) {
+        if (t0 + q * stride < a.T && mn[q] < a.k) {
+          num += (unsigned long long)n * s2[q] - s1[q] * s1[q];
+          cnt += 1;
+        }
       }
     }
   }
