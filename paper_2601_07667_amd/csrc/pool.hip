@@ -12,11 +12,14 @@ constexpr int kPoolRows = 8;       // rows staged together
 
 // A workgroup owns 256 consecutive tokens.  The inputs of up to 8 rows (tile + halo) are staged in
 // LDS with coalesced loads, so every input is read from memory once and its S taps come from LDS;
-// rows are summed in a fixed order.
+// rows are summed in a fixed order.  S_CT: the window length when it is known at compile time (the
+// taps of all staged rows are then read from LDS together), 0 for any other length.
+template <int S_CT>
 __global__ void __launch_bounds__(kPoolBlock)
-pool_kernel(const float* __restrict__ u, int rows, int T, int S, float* __restrict__ p_out,
+pool_kernel(const float* __restrict__ u, int rows, int T, int S_any, float* __restrict__ p_out,
             float* __restrict__ s_out, uint32_t* __restrict__ sample, int n_sample, int sample_stride) {
   __shared__ float tile[kPoolRows][kPoolBlock + 2 * kPoolMaxHalf];
+  const int S = S_CT > 0 ? S_CT : S_any;
   const int h = S / 2;
   const int base = blockIdx.x * kPoolBlock;
   const int t = base + threadIdx.x;
@@ -47,13 +50,32 @@ pool_kernel(const float* __restrict__ u, int rows, int T, int S, float* __restri
     }
     __syncthreads();
     if (t < T) {
-      for (int r = 0; r < nr; ++r) {
-        float acc = 0.f;
-        for (int d = 0; d < S; ++d) acc += tile[r][threadIdx.x + d];   // delta = -h .. +h in order
-        const float p = acc / fS;
-        p_out[(int64_t)(row0 + r) * T + t] = p;
-        if (sampled) sample[(int64_t)(row0 + r) * kSelMaxSample + sample_j] = order_key(p);
-        total += p;
+      if (S_CT > 0) {
+        float p[kPoolRows];
+#pragma unroll
+        for (int r = 0; r < kPoolRows; ++r) {
+          float acc = 0.f;
+#pragma unroll
+          for (int d = 0; d < S_CT; ++d) acc += tile[r][threadIdx.x + d];   // delta = -h .. +h in order
+          p[r] = acc / fS;
+        }
+#pragma unroll
+        for (int r = 0; r < kPoolRows; ++r) {
+          if (r < nr) {
+            p_out[(int64_t)(row0 + r) * T + t] = p[r];
+            if (sampled) sample[(int64_t)(row0 + r) * kSelMaxSample + sample_j] = order_key(p[r]);
+            total += p[r];
+          }
+        }
+      } else {
+        for (int r = 0; r < nr; ++r) {
+          float acc = 0.f;
+          for (int d = 0; d < S; ++d) acc += tile[r][threadIdx.x + d];     // delta = -h .. +h in order
+          const float p = acc / fS;
+          p_out[(int64_t)(row0 + r) * T + t] = p;
+          if (sampled) sample[(int64_t)(row0 + r) * kSelMaxSample + sample_j] = order_key(p);
+          total += p;
+        }
       }
     }
   }
@@ -63,8 +85,13 @@ pool_kernel(const float* __restrict__ u, int rows, int T, int S, float* __restri
 
 hipError_t launch_pool(Prof* prof, const float* u, int rows, int T, int S, float* p_out, float* s_out,
                        uint32_t* sample, hipStream_t st) {
-  ASL_LAUNCH(prof, kKernPool, st, pool_kernel, dim3((T + kPoolBlock - 1) / kPoolBlock), dim3(kPoolBlock), 0, st, u,
-                     rows, T, S, p_out, s_out, sample, sel_sample_size(T), sel_sample_stride(T));
+  const dim3 grid((T + kPoolBlock - 1) / kPoolBlock), block(kPoolBlock);
+  if (S == 7)                                          // the paper's pooling window (App. C.2)
+    ASL_LAUNCH(prof, kKernPool, st, pool_kernel<7>, grid, block, 0, st, u, rows, T, S, p_out, s_out, sample,
+               sel_sample_size(T), sel_sample_stride(T));
+  else
+    ASL_LAUNCH(prof, kKernPool, st, pool_kernel<0>, grid, block, 0, st, u, rows, T, S, p_out, s_out, sample,
+               sel_sample_size(T), sel_sample_stride(T));
   return hipGetLastError();
 }
 

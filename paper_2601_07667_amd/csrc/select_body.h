@@ -26,6 +26,7 @@ __host__ __device__ inline int sel_sample_rank(int T, int k, int n_s, int run) {
 // Without a prepared sample the bound kernel reads runs of kSelSampleRun neighbouring keys, one run
 // per kSelSampleRun sample strides: the same number of keys from a quarter of the cache lines.
 constexpr int kSelSampleRun = 4;
+static_assert(kSelMaxSample % kFinThreads == 0, "the bound kernel's threads share the sample evenly");
 
 // Exclusive prefix over the workgroup's threads of two counters (kFinThreads threads), plus totals.
 __device__ __forceinline__ void block_scan2(uint32_t a, uint32_t b, uint32_t* sm /* 2*kFinWaves+2 */,
@@ -170,17 +171,30 @@ __device__ __forceinline__ void select_guess_body(GuessShared& sh, const SelectA
     if (tid == 0) a.bound[row] = 0xffffffffu;
     return;
   }
+  // Every thread's keys are loaded before the first is stored (positions past the sample re-read its
+  // last key): one memory round trip for the whole sample.
+  constexpr int kSampPer = kSelMaxSample / kFinThreads;
+  uint32_t v[kSampPer];
   if (a.sample != nullptr) {                           // the producer of the scores left the sample behind
-    for (int j = tid; j < n_s; j += kFinThreads) sh.samp[j] = a.sample[(int64_t)row * kSelMaxSample + j];
+    const uint32_t* sp = a.sample + (int64_t)row * kSelMaxSample;
+#pragma unroll
+    for (int u = 0; u < kSampPer; ++u) v[u] = sp[min(tid + u * kFinThreads, n_s - 1)];
   } else {
     const float* sr = a.scores + (int64_t)row * T;
     if (runs) {                                        // key j = member j % run of run j / run
-      for (int j = tid; j < n_s; j += kFinThreads)
-        sh.samp[j] = order_key(sr[(j / kSelSampleRun) * (kSelSampleRun * stride) + (j % kSelSampleRun)]);
+#pragma unroll
+      for (int u = 0; u < kSampPer; ++u) {
+        const int j = min(tid + u * kFinThreads, n_s - 1);
+        v[u] = order_key(sr[(j / kSelSampleRun) * (kSelSampleRun * stride) + (j % kSelSampleRun)]);
+      }
     } else {
-      for (int j = tid; j < n_s; j += kFinThreads) sh.samp[j] = order_key(sr[j * stride]);
+#pragma unroll
+      for (int u = 0; u < kSampPer; ++u) v[u] = order_key(sr[min(tid + u * kFinThreads, n_s - 1) * stride]);
     }
   }
+#pragma unroll
+  for (int u = 0; u < kSampPer; ++u)
+    if (tid + u * kFinThreads < n_s) sh.samp[tid + u * kFinThreads] = v[u];
   uint32_t thr, k_rem;
   radix_select_block(n_s, (uint32_t)m, [&](int i) { return sh.samp[i]; }, sh.h, sh.sm, thr, k_rem);
   if (tid == 0) a.bound[row] = thr;
