@@ -130,7 +130,10 @@ def _stat_case(ctx, dev, R: np.ndarray, l_obs: int, k: int, tau: float, layer_id
 
 
 @pytest.mark.parametrize("n,l_obs,T,k", [(2, 8, 100, 10), (8, 8, 5000, 300), (5, 8, 32736, 992),
-                                         (8, 8, 131040, 2016), (3, 3, 1000, 1000), (8, 8, 262080, 4032)])
+                                         (8, 8, 131040, 2016), (3, 3, 1000, 1000), (8, 8, 262080, 4032),
+                                         # more rows than one load batch holds; rings that wrap part-way
+                                         (12, 12, 3001, 200), (9, 16, 70001, 500), (17, 24, 131073, 640),
+                                         (64, 64, 2500, 100)])
 def test_rankvar_exact(ctx, gpu_device, n, l_obs, T, k):
     rng = np.random.default_rng(n + T)
     base = rng.standard_normal(T)
