@@ -200,6 +200,31 @@ __device__ __forceinline__ void select_guess_body(GuessShared& sh, const SelectA
   if (tid == 0) a.bound[row] = thr;
 }
 
+// key(score) <= bound, decided on the score's bits without forming the key: non-negative scores
+// (bits u < 2^31) have key 2^31 - 1 - u, negative ones key u, and -0 counts as +0.  So for a bound
+// below 2^31 - 1 exactly the bits in [2^31 - 1 - bound, 2^31 - 1] pass, and for any other bound the
+// bits in [0, max(bound, 2^31)] (every non-negative score, -0, and the negative ones up to the
+// bound): one subtraction and one unsigned comparison per score.
+struct KeepTest {
+  uint32_t lo, span;
+};
+__device__ __forceinline__ KeepTest keep_test(uint32_t bound) {
+  KeepTest t;
+  if (bound >= 0x7fffffffu) {
+    t.lo = 0u;
+    t.span = bound > 0x80000000u ? bound : 0x80000000u;
+  } else {
+    t.lo = 0x7fffffffu - bound;
+    t.span = bound;
+  }
+  return t;
+}
+__device__ __forceinline__ bool keeps(const KeepTest& t, float score) { return (__float_as_uint(score) - t.lo) <= t.span; }
+// Set bits of a wavefront ballot that belong to lanes below the calling one.
+__device__ __forceinline__ uint32_t lanes_below(uint64_t ballot) {
+  return __builtin_amdgcn_mbcnt_hi((uint32_t)(ballot >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)ballot, 0u));
+}
+
 struct FilterShared {
   uint32_t wave_tot[kFinWaves];
 };
@@ -217,7 +242,7 @@ __device__ __forceinline__ void select_filter_body(FilterShared& sh, const Selec
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, T = a.T;
   const float* sr = a.scores + (int64_t)row * T;
   const int base = tile * kSelTile + wave * kSelPerWave;
-  uint32_t key[kSelRounds][kPer];
+  float sc[kSelRounds][kPer];
 #pragma unroll
   for (int r = 0; r < kSelRounds; ++r) {               // all loads in flight before the first use
     const int e = base + (r * 64 + lane) * kPer;
@@ -230,23 +255,34 @@ __device__ __forceinline__ void select_filter_body(FilterShared& sh, const Selec
         if (e + 1 < T) v.y = sr[e + 1];
         if (e + 2 < T) v.z = sr[e + 2];
       }
-      key[r][0] = order_key(v.x);
-      key[r][1 % kPer] = order_key(v.y);
-      key[r][2 % kPer] = order_key(v.z);
-      key[r][3 % kPer] = order_key(v.w);
+      sc[r][0] = v.x;
+      sc[r][1 % kPer] = v.y;
+      sc[r][2 % kPer] = v.z;
+      sc[r][3 % kPer] = v.w;
     } else {
-      key[r][0] = (e < T) ? order_key(sr[e]) : 0u;
+      sc[r][0] = (e < T) ? sr[e] : 0.f;
     }
   }
-  const uint32_t b = a.bound[row];
+  const KeepTest kt = keep_test(a.bound[row]);
+  // per round: which of the lane's tokens are kept (bit j), how many lower lanes keep, the round's total
+  uint32_t kept[kSelRounds], before[kSelRounds], round_tot[kSelRounds];
   uint32_t w_cnt = 0;
 #pragma unroll
-  for (int r = 0; r < kSelRounds; ++r)
+  for (int r = 0; r < kSelRounds; ++r) {
+    const int e0 = base + (r * 64 + lane) * kPer;
+    kept[r] = 0;
+    before[r] = 0;
+    round_tot[r] = 0;
 #pragma unroll
     for (int j = 0; j < kPer; ++j) {
-      const bool keep = (base + (r * 64 + lane) * kPer + j < T) && key[r][j] <= b;
-      w_cnt += __popcll(__ballot(keep));
+      const bool keep = (e0 + j < T) && keeps(kt, sc[r][j]);
+      const uint64_t bal = __ballot(keep);
+      kept[r] |= keep ? (1u << j) : 0u;
+      before[r] += lanes_below(bal);
+      round_tot[r] += (uint32_t)__popcll(bal);
     }
+    w_cnt += round_tot[r];
+  }
   if (lane == 0) sh.wave_tot[wave] = w_cnt;
   __syncthreads();
   uint32_t run = 0, total = 0;
@@ -259,30 +295,21 @@ __device__ __forceinline__ void select_filter_body(FilterShared& sh, const Selec
   if (total > (uint32_t)kSelSegment) return;           // uniform: the finish step takes the whole row instead
   uint32_t* ck = a.cand_key + seg * kSelSegment;
   uint32_t* ci = a.cand_idx + seg * kSelSegment;
-  const uint64_t lt_mask = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
 #pragma unroll
   for (int r = 0; r < kSelRounds; ++r) {
+    // token order inside a round: lane by lane, a lane's kPer tokens in a row.  Few tokens are kept:
+    // the loop runs as often as the busiest lane has kept tokens.
     const int e0 = base + (r * 64 + lane) * kPer;
-    // token order inside a round: lane by lane, a lane's kPer tokens in a row
-    bool keep[kPer];
-    uint32_t before = 0, round_tot = 0;                 // kept by lower lanes / by the whole wavefront
-#pragma unroll
-    for (int j = 0; j < kPer; ++j) {
-      keep[j] = (e0 + j < T) && key[r][j] <= b;
-      const uint64_t bal = __ballot(keep[j]);
-      before += (uint32_t)__popcll(bal & lt_mask);
-      round_tot += (uint32_t)__popcll(bal);
+    uint32_t pos = run + before[r], m = kept[r];
+    while (m != 0u) {
+      const int j = __ffs((int)m) - 1;
+      const float f = (j == 0) ? sc[r][0] : (j == 1) ? sc[r][1 % kPer] : (j == 2) ? sc[r][2 % kPer] : sc[r][3 % kPer];
+      ck[pos] = order_key(f);
+      ci[pos] = (uint32_t)(e0 + j);
+      ++pos;
+      m &= m - 1u;
     }
-    uint32_t pos = run + before;
-#pragma unroll
-    for (int j = 0; j < kPer; ++j) {
-      if (keep[j]) {
-        ck[pos] = key[r][j];
-        ci[pos] = (uint32_t)(e0 + j);
-        ++pos;
-      }
-    }
-    run += round_tot;
+    run += round_tot[r];
   }
 }
 

@@ -221,18 +221,77 @@ def test_rank_select_pool_random_shapes(ctx, gpu_device):
         _select_case(ctx, gpu_device, s, budget, W)
 
 
-@pytest.mark.parametrize("rows,T,budget", [(96, 100000, 1056), (96, 100001, 1056), (300, 9000, 532)])
+@pytest.mark.parametrize("rows,T,budget", [(96, 100000, 1056), (96, 100001, 1056), (300, 9000, 532),
+                                           (128, 131040, 2080), (130, 100001, 1056), (256, 20000, 8192),
+                                           (129, 70000, 35000), (128, 5, 4), (140, 4096, 33)])
 def test_select_many_rows(gpu_device, rows, T, budget):
     """96 rows x 25 tiles: the tile count from which the filter stage runs as many small workgroups
     (a few rows take one round of large ones); with T a multiple of four the rows are read four scores
     per load, with T = 100001 one at a time.  300 rows: more than the candidate buffers hold at once,
-    so the three launches run twice."""
-    W = 32
-    rng = np.random.default_rng(rows)
+    so the three launches run twice.  Further: 128 full-size rows, a budget of 8192 on many rows, a
+    budget of half the row (the candidates overflow: selection from the whole row), rows of five
+    tokens, rows of exactly one tile."""
+    W = 32 if T > 100 else 2
+    rng = np.random.default_rng(rows + T)
     s = np.round(rng.random((rows, T), dtype=np.float32), 4).astype(np.float32)
     c = asl.Asl(T + W, rows, rows * W)
     try:
         _select_case(c, gpu_device, s, budget, W)
+        assert c.asl_device_fault() == 0
+    finally:
+        c.close()
+
+
+def test_select_many_hard_rows(gpu_device):
+    """Many rows at once whose sampled bound is useless or whose candidates overflow (top tokens
+    clustered at either end or inside one tile, a few distinct values, all equal, sorted either way,
+    negative scores), several of each kind in one call, beside ordinary rows."""
+    rng = np.random.default_rng(77)
+    rows, T, W, budget = 144, 70000, 32, 2048
+    s = rng.random((rows, T), dtype=np.float32)
+    for r in range(rows):
+        kind = r % 9
+        if kind == 1:
+            s[r, :3000] += 10.0
+        elif kind == 2:
+            s[r, -3000:] += 10.0
+        elif kind == 3:
+            s[r] = rng.integers(0, 4, T).astype(np.float32)
+        elif kind == 4:
+            s[r] = 0.25
+        elif kind == 5:
+            s[r] = np.sort(s[r])[::-1]
+        elif kind == 6:
+            s[r] = np.sort(s[r])
+        elif kind == 7:
+            s[r, 16384:20480] = 5.0 + rng.random(4096, dtype=np.float32)
+        elif kind == 8:
+            s[r] = -s[r] - 1.0
+    c = asl.Asl(T + W, rows, rows * W)
+    try:
+        _select_case(c, gpu_device, np.ascontiguousarray(s), budget, W)
+        _select_case(c, gpu_device, np.ascontiguousarray(s), W + 1, W)             # k = 1
+        _select_case(c, gpu_device, np.ascontiguousarray(s[:, :3000]), 4000, W)    # budget >= N: keep all
+        assert c.asl_device_fault() == 0
+    finally:
+        c.close()
+
+
+@pytest.mark.parametrize("rows", [3, 130])
+def test_select_around_zero(gpu_device, rows):
+    """Scores drawn from a few values on both sides of zero (+0, -0, denormals of either sign, small
+    and large magnitudes), so that for one budget or another the threshold falls on each of them:
+    -0 and +0 tie (lower index first), denormals do not count as zero, negative scores order by
+    magnitude downwards (the filter decides on the scores' bits: every sign and zero case matters)."""
+    rng = np.random.default_rng(rows)
+    T, W = 20000, 16
+    vals = np.array([0.0, -0.0, 1e-40, -1e-40, 1e-45, -1e-45, 1.0, -1.0, 3e38, -3e38, 1e-20, -1e-20], dtype=np.float32)
+    s = vals[rng.integers(0, len(vals), (rows, T))]
+    assert np.signbit(s).any() and (s == 0).any()
+    c = asl.Asl(T + W, rows, rows * W)
+    try:
+        for k in (1, 900, 1700, 2500, 3400, 5000, 8400, 10000, 12000, 15000, 19999):
+            _select_case(c, gpu_device, s, k + W, W)
         assert c.asl_device_fault() == 0
     finally:
         c.close()
