@@ -132,6 +132,56 @@ __device__ __forceinline__ uint32_t order_key(float f) {
   return ~asc;
 }
 
+// Inclusive prefix sum over the 64 lanes of a wavefront (all of them active), by data-parallel
+// moves inside the vector ALU: within each row of 16 lanes by shifts of 1, 2, 4 and 8 lanes (a lane
+// without a source adds 0), then the last lane of rows 0 and 2 to rows 1 and 3, then lane 31 to rows
+// 2 and 3.  (A shuffle-based scan goes through the LDS crossbar six times, ~100 cycles each.)
+__device__ __forceinline__ uint32_t wave_prefix_sum(uint32_t x) {
+  x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x111, 0xf, 0xf, false);   // row_shr:1
+  x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x112, 0xf, 0xf, false);   // row_shr:2
+  x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x114, 0xf, 0xf, false);   // row_shr:4
+  x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x118, 0xf, 0xf, false);   // row_shr:8
+  x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x142, 0xa, 0xf, false);   // row_bcast:15 into rows 1, 3
+  x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x143, 0xc, 0xf, false);   // row_bcast:31 into rows 2, 3
+  return x;
+}
+
+// Minimum / maximum over the 64 lanes of a wavefront (all active), the same way; every lane gets the
+// result.  Lanes without a source take the operation's identity.
+__device__ __forceinline__ uint32_t wave_min(uint32_t x) {
+#define ASL_DPP_MIN_(ctrl, rows) x = min(x, (uint32_t)__builtin_amdgcn_update_dpp(-1, (int)x, ctrl, rows, 0xf, false))
+  ASL_DPP_MIN_(0x111, 0xf);
+  ASL_DPP_MIN_(0x112, 0xf);
+  ASL_DPP_MIN_(0x114, 0xf);
+  ASL_DPP_MIN_(0x118, 0xf);
+  ASL_DPP_MIN_(0x142, 0xa);
+  ASL_DPP_MIN_(0x143, 0xc);
+#undef ASL_DPP_MIN_
+  return (uint32_t)__builtin_amdgcn_readlane((int)x, 63);
+}
+__device__ __forceinline__ uint32_t wave_max(uint32_t x) {
+#define ASL_DPP_MAX_(ctrl, rows) x = max(x, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, ctrl, rows, 0xf, false))
+  ASL_DPP_MAX_(0x111, 0xf);
+  ASL_DPP_MAX_(0x112, 0xf);
+  ASL_DPP_MAX_(0x114, 0xf);
+  ASL_DPP_MAX_(0x118, 0xf);
+  ASL_DPP_MAX_(0x142, 0xa);
+  ASL_DPP_MAX_(0x143, 0xc);
+#undef ASL_DPP_MAX_
+  return (uint32_t)__builtin_amdgcn_readlane((int)x, 63);
+}
+// Sum of a 32-bit / a 64-bit value over the 64 lanes (all active); every lane gets the result.  The
+// 64-bit sum goes through three 22-bit limbs, whose 64-lane sums fit 32 bits.
+__device__ __forceinline__ uint32_t wave_sum(uint32_t x) {
+  return (uint32_t)__builtin_amdgcn_readlane((int)wave_prefix_sum(x), 63);
+}
+__device__ __forceinline__ unsigned long long wave_sum(unsigned long long x) {
+  const uint32_t m22 = (1u << 22) - 1u;
+  const unsigned long long l0 = wave_sum((uint32_t)x & m22), l1 = wave_sum((uint32_t)(x >> 22) & m22),
+                           l2 = wave_sum((uint32_t)(x >> 44));       // x < 2^64: the top limb has 20 bits
+  return l0 + (l1 << 22) + (l2 << 44);
+}
+
 __device__ __forceinline__ void hist_clear(uint32_t* h, int tid, int n_threads) {
   for (int i = tid; i < kHistWords; i += n_threads) h[i] = 0;
 }

@@ -124,12 +124,7 @@ __device__ __forceinline__ void sort_pass_body(SortShared& sh, const SortArgs& a
       tot += sh.part_tot[g][tid];
       prev += sh.part_prev[g][tid];
     }
-    uint32_t incl = tot;
-#pragma unroll
-    for (int o = 1; o < 64; o <<= 1) {
-      uint32_t up = __shfl_up(incl, o);
-      if (lane >= o) incl += up;
-    }
+    const uint32_t incl = wave_prefix_sum(tot);
     if (lane == 63) sh.wave_sum[wave] = incl;
     sh.part_tot[0][tid] = incl - tot;                   // exclusive within the wave (own group row is consumed)
     sh.part_prev[0][tid] = prev;

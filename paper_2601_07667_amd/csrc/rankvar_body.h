@@ -109,10 +109,8 @@ __device__ __forceinline__ void rankvar_body(RankvarShared& sh, const RankvarArg
       }
     }
   }
-  for (int o = 32; o > 0; o >>= 1) {
-    num += __shfl_down(num, o);
-    cnt += __shfl_down(cnt, o);
-  }
+  num = wave_sum(num);
+  cnt = wave_sum(cnt);
   if ((tid & 63) == 0) {
     sh.red_num[tid >> 6] = num;
     sh.red_cnt[tid >> 6] = cnt;
@@ -147,10 +145,8 @@ __device__ __forceinline__ void rankvar_body(RankvarShared& sh, const RankvarArg
     total += piece0 | (piece1 << 28) | ((unsigned long long)flag_count0(v[2]) << 56);
     m += flag_count0(v[3]) | (flag_count1(v[3]) << 14);
   }
-  for (int o = 32; o > 0; o >>= 1) {
-    total += __shfl_down(total, o);
-    m += __shfl_down(m, o);
-  }
+  total = wave_sum(total);
+  m = wave_sum(m);
   if ((tid & 63) == 0) {
     sh.red_num[tid >> 6] = total;
     sh.red_cnt[tid >> 6] = m;

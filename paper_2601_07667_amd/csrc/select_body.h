@@ -32,15 +32,7 @@ static_assert(kSelMaxSample % kFinThreads == 0, "the bound kernel's threads shar
 __device__ __forceinline__ void block_scan2(uint32_t a, uint32_t b, uint32_t* sm /* 2*kFinWaves+2 */,
                                             uint32_t& a_excl, uint32_t& b_excl, uint32_t& a_tot, uint32_t& b_tot) {
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-  uint32_t ai = a, bi = b;
-#pragma unroll
-  for (int o = 1; o < 64; o <<= 1) {
-    const uint32_t ua = __shfl_up(ai, o), ub = __shfl_up(bi, o);
-    if (lane >= o) {
-      ai += ua;
-      bi += ub;
-    }
-  }
+  const uint32_t ai = wave_prefix_sum(a), bi = wave_prefix_sum(b);
   __syncthreads();                                     // sm may still be in use
   if (lane == 63) {
     sm[wave] = ai;
@@ -77,12 +69,8 @@ __device__ __forceinline__ void radix_select_block(int n, uint32_t k, KeyAt key_
     lo = key < lo ? key : lo;
     hi = key > hi ? key : hi;
   }
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) {
-    const uint32_t l2 = __shfl_xor(lo, o), h2 = __shfl_xor(hi, o);
-    lo = l2 < lo ? l2 : lo;
-    hi = h2 > hi ? h2 : hi;
-  }
+  lo = wave_min(lo);
+  hi = wave_max(hi);
   __syncthreads();                                     // sm may still be in use
   if (lane == 0) {
     sm[wave] = lo;
@@ -113,12 +101,7 @@ __device__ __forceinline__ void radix_select_block(int n, uint32_t k, KeyAt key_
     uint32_t cnt = 0, incl = 0;
     if (tid < 256) {
       cnt = hist_total(h, tid);
-      incl = cnt;
-#pragma unroll
-      for (int o = 1; o < 64; o <<= 1) {
-        const uint32_t up = __shfl_up(incl, o);
-        if (lane >= o) incl += up;
-      }
+      incl = wave_prefix_sum(cnt);
       if (lane == 63) sm[wave] = incl;
     }
     if (tid == 0) {
