@@ -59,15 +59,23 @@ __device__ __forceinline__ void block_scan2(uint32_t a, uint32_t b, uint32_t* sm
 // key - min over the bits in which min and max differ, so the first digit already spreads the keys
 // over the bins (scores of one row share their sign and most of their exponent).
 // h: kHistWords-word LDS histogram (bank-staggered copies), sm: >= 2 * kFinWaves + 2 words.
+constexpr int kSelBatch = 4;                           // keys a thread reads together in the selection loops
 template <typename KeyAt>
 __device__ __forceinline__ void radix_select_block(int n, uint32_t k, KeyAt key_at, uint32_t* h, uint32_t* sm,
                                                    uint32_t& thr_out, uint32_t& k_rem_out) {
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  // The loops over the keys take kSelBatch of a thread's keys at a time (positions past the end
+  // re-read the thread's first key of the batch), so that their reads are in flight together.
   uint32_t lo = 0xffffffffu, hi = 0u;
-  for (int i = tid; i < n; i += kFinThreads) {
-    const uint32_t key = key_at(i);
-    lo = key < lo ? key : lo;
-    hi = key > hi ? key : hi;
+  for (int i0 = tid; i0 < n; i0 += kSelBatch * kFinThreads) {
+    uint32_t key[kSelBatch];
+#pragma unroll
+    for (int u = 0; u < kSelBatch; ++u) key[u] = key_at(i0 + u * kFinThreads < n ? i0 + u * kFinThreads : i0);
+#pragma unroll
+    for (int u = 0; u < kSelBatch; ++u) {
+      lo = key[u] < lo ? key[u] : lo;
+      hi = key[u] > hi ? key[u] : hi;
+    }
   }
   lo = wave_min(lo);
   hi = wave_max(hi);
@@ -91,9 +99,13 @@ __device__ __forceinline__ void radix_select_block(int n, uint32_t k, KeyAt key_
     __syncthreads();                                   // h and sm of the previous pass are consumed
     hist_clear(h, tid, kFinThreads);
     __syncthreads();
-    for (int i = tid; i < n; i += kFinThreads) {
-      const uint32_t v = key_at(i) - lo;
-      if (pass == 0 || (v >> (shift + 8)) == prefix) hist_add(h, tid, (v >> shift) & 255u);
+    for (int i0 = tid; i0 < n; i0 += kSelBatch * kFinThreads) {
+      uint32_t v[kSelBatch];
+#pragma unroll
+      for (int u = 0; u < kSelBatch; ++u) v[u] = key_at(i0 + u * kFinThreads < n ? i0 + u * kFinThreads : i0) - lo;
+#pragma unroll
+      for (int u = 0; u < kSelBatch; ++u)
+        if (i0 + u * kFinThreads < n && (pass == 0 || (v[u] >> (shift + 8)) == prefix)) hist_add(h, tid, (v[u] >> shift) & 255u);
     }
     __syncthreads();
     // exclusive scan of the 256 counts by the first four wavefronts; the digit d with
