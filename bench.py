@@ -495,8 +495,10 @@ def main() -> int:
                    "launch": launch + ("; single calls back to back on one stream" if args.one_stream else
                                        ("; ranking+statistic on the launch stream, top-k+gather on a second stream, a step's "
                                         "top-k+gather may still run while the next step scores" if args.defer_join else
-                                        "; asl_layer_step on one stream (8 launches: 2 scoring passes, pooling, 5 launches "
-                                        "that each carry a ranking and a top-k / statistic / compaction stage)")),
+                                        "; asl_layer_step on one stream (" +
+                                        ("7 launches: 1 scoring pass" if args.lse else "8 launches: 2 scoring passes") +
+                                        ", pooling, 5 launches that each carry a ranking and a top-k / statistic / "
+                                        "compaction stage)")),
                    "eager_profiled_ms_per_step": round(eager_profiled_ms, 5),
                    "step": "asl_layer_step = score_layer + rank_stat(full ring) + select_topk(Hk per-head rows + the all-head row) + gather_kv(K,V per head)"},
         "roofline": roofline, "cpu_baseline": cpu, "roofline_by_kernel": by_kernel,
