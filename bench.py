@@ -177,12 +177,17 @@ def main() -> int:
         del src, dst
 
     # Timed region: exactly `steps` steps.  By default they are replayed from HIP graphs, which takes
-    # the host's launch cost out of the measurement: one graph holds L_obs consecutive layers (one trip
-    # round the rank ring) and is replayed steps // L_obs times; if steps is not a multiple of L_obs a
-    # second graph holds the remaining steps % L_obs layers and is replayed once at the end.
-    # --eager launches every kernel from Python instead.
+    # the host's launch cost out of the measurement.  One trip round the rank ring (L_obs consecutive
+    # layers) is captured twice: as graphs of GRAPH_STEPS layers and as graphs of one layer each.
+    # The timed region replays the larger graphs in ring order, steps // GRAPH_STEPS times, and the
+    # single-layer graphs for the remaining steps, so every step continues the ring of the step
+    # before whatever the step count.  (Small graphs: the device starts on a graph only when the host
+    # has submitted all of it, ~2.7 us per kernel, which a run of few steps would otherwise wait for;
+    # later graphs are submitted while earlier ones run.)  --eager launches every kernel from Python.
     use_graph = not args.eager and args.steps >= sh.L_obs
-    n_trips, n_rest = divmod(args.steps, sh.L_obs)
+    GRAPH_STEPS = 4 if sh.L_obs % 4 == 0 else 1
+    STEADY_TRIPS = 16
+    n_big, n_single = divmod(args.steps, GRAPH_STEPS)
 
     def next_layer() -> int:
         return asl.read_struct(state, asl.AslState).last_layer + 1
@@ -190,33 +195,34 @@ def main() -> int:
     if use_graph:
         cap_stream = torch.cuda.Stream()
         cap_stream.wait_stream(torch.cuda.current_stream())
-        graphs = []
         with torch.cuda.stream(cap_stream):
             base = next_layer()
-            gr = torch.cuda.CUDAGraph()
-            with torch.cuda.graph(gr, stream=cap_stream):
-                for j in range(sh.L_obs):
-                    step(base + j)
-                ctx.asl_join()                         # a capture must end with every forked stream joined
-            graphs.append((gr, n_trips))
-            if n_rest:
+
+            def capture(first: int, count: int):
                 gr = torch.cuda.CUDAGraph()
                 with torch.cuda.graph(gr, stream=cap_stream):
-                    for j in range(n_rest):
-                        step(base + sh.L_obs + j)
-                    ctx.asl_join()
-                graphs.append((gr, 1))
-            # captured work has not run yet: warm both graphs once in their order, then replay the trip
-            # graph once more so that the timed replays continue a full ring (a trip whose first layer
-            # does not follow the ring's last one restarts the ring and refills all L_obs rows)
-            for gr, _ in graphs:
+                    for j in range(count):
+                        step(base + first + j)
+                    ctx.asl_join()                     # a capture must end with every forked stream joined
+                return gr
+
+            big = [capture(j, GRAPH_STEPS) for j in range(0, sh.L_obs, GRAPH_STEPS)]
+            single = [capture(j, 1) for j in range(sh.L_obs)]
+            # captured work has not run yet: one trip through each set warms every graph and leaves
+            # the ring where the first timed graph continues it
+            for gr in big + single:
                 gr.replay()
-            graphs[0][0].replay()
+            # then whole trips until the device has been busy for ~20 ms, so that a short timed
+            # region does not start on clocks that dropped while the host was capturing
+            for _ in range(STEADY_TRIPS):
+                for gr in big:
+                    gr.replay()
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        for gr, reps in graphs:
-            for _ in range(reps):
-                gr.replay()
+        for i in range(n_big):
+            big[i % len(big)].replay()
+        for i in range(n_single):
+            single[(n_big * GRAPH_STEPS + i) % sh.L_obs].replay()
         torch.cuda.synchronize()
         t1 = time.perf_counter()
     else:
@@ -478,8 +484,8 @@ def main() -> int:
                 5: "C5: Llama-3-8B shape, N=262144, W=64, S=7, budget 4096, heavy-tailed keys + 256 needles",
                 6: "second model shape (Hq28/Hk4/d128: 224 query rows per KV head), N=131072, W=32, S=7, budget 8192"}
     if use_graph:
-        launch = (f"HIP graph replay: {n_trips} x a graph of {sh.L_obs} layers" +
-                  (f" + 1 x a graph of {n_rest} layers" if n_rest else ""))
+        launch = (f"HIP graph replay: {n_big} x a graph of {GRAPH_STEPS} layers" +
+                  (f" + {n_single} x a graph of 1 layer" if n_single else ""))
     else:
         launch = "eager launches from Python"
     line = {
